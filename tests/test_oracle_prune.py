@@ -1,0 +1,76 @@
+"""Pins for the oracle's pruning (Sec. 3.4)."""
+import numpy as np
+
+from oracle import prune, tree
+
+
+def test_parent_top1_keeps_one_child_per_last_split_parent():
+    t = tree.tree_build(6, (0, 2, 4), 2)                     # 8 leaves
+    r = np.array([0.1, 0.9, 0.5, 0.4, -1.0, -1.0, 2.0, 3.0], np.float32)
+    keep = prune.width_keep_leaves(t, r, 1)
+    assert list(np.nonzero(keep)[0]) == [1, 2, 4, 7]         # tie (-1, -1) -> lower branch index
+    assert keep.sum() == t["n_leaves"] // t["K"]             # "roughly halves" for K = 2
+    t3 = tree.tree_build(4, (1, 2), 3)
+    r3 = np.random.default_rng(0).standard_normal(9).astype(np.float32)
+    k3 = prune.width_keep_leaves(t3, r3, 1)
+    assert k3.sum() == 3 and all(k3[3 * p + np.argmax(r3[3 * p:3 * p + 3])] for p in range(3))
+
+
+def test_extreme_b_hand_values():
+    t = tree.tree_build(6, (0, 2, 4), 2)
+    r = np.array([0.5, -2.0, 0.5, 3.0, 0.0, 0.5, -1.0, 2.5], np.float32)
+    assert list(np.nonzero(prune.width_keep_leaves(t, r, 2, 2))[0]) == [1, 3, 6, 7]
+    # ties among (0.5, 0.5, 0.5) are ordered by leaf index: b = 3 -> worst {1, 6, 4}, best {5, 7, 3}
+    assert list(np.nonzero(prune.width_keep_leaves(t, r, 2, 3))[0]) == [1, 3, 4, 5, 6, 7]
+    assert prune.width_keep_leaves(t, r, 2, 4).all() and prune.width_keep_leaves(t, r, 0).all()
+
+
+def _paths_union(t, leaves):
+    e = set()
+    for l in leaves:
+        n = t["off"][t["T"]] + l
+        while t["parent"][n] >= 0:
+            e.add(int(n))
+            n = t["parent"][n]
+    return e
+
+
+def test_kept_edges_are_the_union_of_root_to_leaf_paths():
+    t = tree.tree_build(7, (1, 3, 4), 2)
+    rng = np.random.default_rng(1)
+    C = 3
+    r = rng.standard_normal(C * t["n_leaves"]).astype(np.float32)
+    none = np.zeros(t["T"], np.uint8)
+    for mode, b in ((0, 0), (1, 0), (2, 1), (2, 3)):
+        got = prune.kept_edges(t, r, C, mode, b, none)
+        exp = []
+        for c in range(C):
+            keep = prune.width_keep_leaves(t, r.reshape(C, -1)[c], mode, b)
+            exp += sorted(c * t["n_nodes"] + n for n in _paths_union(t, np.nonzero(keep)[0]))
+        assert list(got) == exp and got.dtype == np.int32
+    # no pruning at all keeps every edge
+    assert len(prune.kept_edges(t, r, C, 0, 0, none)) == C * t["n_edges"]
+    # depth mask removes exactly the edges of the masked steps
+    mask = np.zeros(t["T"], np.uint8)
+    mask[[0, 5]] = 1
+    got = prune.kept_edges(t, r, C, 0, 0, mask)
+    assert all(t["depth"][g % t["n_nodes"]] - 1 not in (0, 5) for g in got)
+    assert len(got) == C * (t["n_edges"] - t["width"][1] - t["width"][6])
+
+
+def test_sliding_window_schedule():
+    # Sec. 4.4: starts at the last split, size 4, moves one step every 30 iterations
+    m = prune.depth_mask_window(20, 9, 4, 0, 30, 20)
+    assert list(np.nonzero(m)[0]) == [9, 10, 11, 12]
+    assert list(np.nonzero(prune.depth_mask_window(20, 9, 4, 29, 30, 20))[0]) == [9, 10, 11, 12]
+    assert list(np.nonzero(prune.depth_mask_window(20, 9, 4, 30, 30, 20))[0]) == [10, 11, 12, 13]
+    assert list(np.nonzero(prune.depth_mask_window(20, 9, 4, 300, 30, 20))[0]) == [16, 17, 18, 19]   # stops
+    assert list(np.nonzero(prune.depth_mask_window(20, 9, 4, 3000, 30, 18))[0]) == [14, 15, 16, 17]
+
+
+def test_seeded_depth_subset():
+    m = prune.depth_mask_seeded(20, 4, 42)
+    assert m.sum() == 4 and m.dtype == np.uint8
+    assert np.array_equal(m, prune.depth_mask_seeded(20, 4, 42))
+    assert not np.array_equal(m, prune.depth_mask_seeded(20, 4, 43))
+    assert prune.depth_mask_seeded(20, 0, 42).sum() == 0 and prune.depth_mask_seeded(5, 5, 1).all()
