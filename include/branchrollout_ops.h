@@ -1,0 +1,45 @@
+/*
+ * libbranchrollout -- op-level entry points of the velocity network, for checking
+ * single kernels against a reference and for timing them in isolation.  They are
+ * not part of the rollout API; conventions as in branchrollout.h.
+ */
+#ifndef BRANCHROLLOUT_OPS_H
+#define BRANCHROLLOUT_OPS_H
+
+#include "branchrollout.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[m, n] = epilogue(sum_k A[m, k] W[n, k] + bias[n]); A dev [M, lda], W dev [N, ldw]
+ * in `dtype` (BR_F32 / BR_BF16), bias dev [N] fp32.
+ *   epilogue 0: out[m, n] = acc                  out in `dtype`  [M, ldo]
+ *            1: out[m, n] = gelu_tanh(acc)       out in `dtype`
+ *            2: out[m, n] += gate[cond[m / L]][n] * acc    out fp32 in place;
+ *               gate row r at mods + r*mods_stride + gate_off, cond dev [M / L]
+ *            4: out[m, n] = acc                  out fp32
+ * BR_BF16 needs K % 64 == 0, lda % 8 == 0, ldw % 8 == 0; N % 4 == 0 always.
+ * variant: tile shape of the bf16 kernel (-1 = automatic, 0..3). */
+br_status br_op_gemm(int32_t dtype, int32_t epilogue, const void* A, int32_t lda, const void* W,
+                     int32_t ldw, int32_t M, int32_t N, int32_t K, const float* bias, void* out,
+                     int32_t ldo, const float* mods, int32_t mods_stride, int32_t gate_off,
+                     const int32_t* cond, int32_t L, int32_t variant, void* stream);
+
+/* out[b, l, h*DH + d] = softmax_j(q_l . k_j / sqrt(DH)) v_j for every sample b and
+ * head h; qkv dev [B, L, 3*NH*DH] (q | k | v), out dev [B, L, NH*DH], both `dtype`. */
+br_status br_op_attention(int32_t dtype, const void* qkv, void* out, int32_t B, int32_t L,
+                          int32_t NH, int32_t DH, void* stream);
+
+/* out[r, :] = LayerNorm(x[src(r), :]) * (1 + scale) + shift, eps 1e-6, no affine;
+ * r = b*rows_per_sample + tok, src(r) = b*L_in + tok; shift / scale are the rows
+ * mods + cond[b]*mods_stride + {shift_off, scale_off}.  x dev fp32, out dev `dtype`. */
+br_status br_op_ln_modulate(int32_t dtype, const float* x, void* out, int32_t n_rows,
+                            int32_t rows_per_sample, int32_t L_in, int32_t H, const float* mods,
+                            int32_t mods_stride, int32_t shift_off, int32_t scale_off,
+                            const int32_t* cond, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

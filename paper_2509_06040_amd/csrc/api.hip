@@ -1,0 +1,318 @@
+// C-ABI entry points and the frontier scheduler: per step, all nodes of one depth
+// (over all trees) go through the network as one batch, so shared prefixes are
+// evaluated once (Alg. 1, tree-building loop; Sec. 1 "shared prefixes amortize
+// computation").
+#include <algorithm>
+#include <cmath>
+
+#include "common.h"
+#include "dit.h"
+#include "kernels.h"
+
+using namespace br;
+
+namespace {
+
+br_status check_sched(const br_tree* tree, const br_sched* s, const char* who) {
+  BR_REQUIRE(s && s->t && s->sigma, BR_EINVAL, std::string(who) + ": schedule or its arrays are NULL");
+  BR_REQUIRE(s->T == tree->T, BR_EINVAL, std::string(who) + ": schedule T differs from the tree's");
+  for (int i = 0; i < s->T; ++i) {
+    BR_REQUIRE(std::isfinite(s->t[i]) && s->t[i] > 0.f && s->t[i] > s->t[i + 1], BR_EINVAL,
+               std::string(who) + ": t must be strictly decreasing and positive before the last entry");
+    BR_REQUIRE(std::isfinite(s->sigma[i]) && s->sigma[i] >= 0.f, BR_EINVAL, std::string(who) + ": sigma must be >= 0");
+  }
+  BR_REQUIRE(std::isfinite(s->t[s->T]) && s->t[s->T] >= 0.f, BR_EINVAL, std::string(who) + ": t[T] must be >= 0");
+  BR_REQUIRE(std::isfinite(s->s) && s->s >= 0.f, BR_EINVAL, std::string(who) + ": branch correlation s must be >= 0");
+  BR_REQUIRE(s->logp_reduce == BR_LOGP_SUM || s->logp_reduce == BR_LOGP_MEAN, BR_EINVAL,
+             std::string(who) + ": unknown logp_reduce");
+  return BR_OK;
+}
+
+int max_frontier(const br_tree* t) {  // widest batch that ever goes through the network
+  int w = 1;
+  for (int i = 0; i < t->T; ++i) w = std::max(w, t->width[i]);
+  return w * t->n_tree;
+}
+
+struct Sizes {
+  int n_cond;
+  long long v_rows, partial_floats, plan_ints;
+};
+
+Sizes sizes_for(const br_tree* t, const br_model* m, int max_batch) {
+  Sizes s;
+  if (t) {
+    s.n_cond = t->n_tree;
+    s.v_rows = max_frontier(t);
+    s.partial_floats = (long long)t->n_tree * t->n_leaves * sde_nblk(m->D);
+    s.plan_ints = 6LL * t->n_tree * t->n_nodes + max_batch;
+  } else {
+    s.n_cond = max_batch;
+    s.v_rows = 0;
+    s.partial_floats = 0;
+    s.plan_ints = max_batch;
+  }
+  return s;
+}
+
+// Largest batch (<= want) whose plan fits into `bytes`; 0 if none.
+int fit_batch(const br_tree* t, const br_model* m, int want, size_t bytes, int n_cond_override) {
+  int lo = 0, hi = want;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) / 2;
+    Sizes s = sizes_for(t, m, t ? mid : want);
+    if (n_cond_override > 0) s.n_cond = n_cond_override;
+    if (plan_workspace(m, s.n_cond, mid, s.v_rows, s.partial_floats, s.plan_ints, nullptr, nullptr) <= bytes) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+
+}  // namespace
+
+extern "C" size_t br_workspace_bytes(const br_tree* tree, const br_model* model, int32_t max_batch) {
+  if (!model || max_batch < 1) return 0;
+  const Sizes s = sizes_for(tree, model, max_batch);
+  return plan_workspace(model, s.n_cond, max_batch, s.v_rows, s.partial_floats, s.plan_ints, nullptr, nullptr);
+}
+
+extern "C" br_status br_rollout(const br_tree* tree, const br_model* model, const br_sched* sched, uint64_t seed,
+                                const int32_t* noise_group, const void* cond_tokens, float* z_nodes, float* logp_edges,
+                                float* v_nodes, void* workspace, size_t workspace_bytes, void* stream) {
+  BR_REQUIRE(tree && model && noise_group && cond_tokens && z_nodes && logp_edges && workspace, BR_EINVAL,
+             "br_rollout: NULL argument");
+  br_status s;
+  if ((s = check_sched(tree, sched, "br_rollout")) != BR_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  const int mb = fit_batch(tree, model, max_frontier(tree), workspace_bytes, 0);
+  BR_REQUIRE(mb >= 1, BR_EWORKSPACE, "br_rollout: workspace too small (see br_workspace_bytes)");
+  FwdBuffers fb;
+  const Sizes sz = sizes_for(tree, model, mb);
+  plan_workspace(model, sz.n_cond, mb, sz.v_rows, sz.partial_floats, sz.plan_ints, &fb, workspace);
+  const long long D = model->D;
+  if ((s = launch_fill_zero(logp_edges, (long long)tree->n_tree * tree->n_nodes, st)) != BR_OK) return s;
+  if ((s = launch_root_noise(tree, seed, noise_group, D, z_nodes, st)) != BR_OK) return s;
+  if ((s = embed_cond(model, fb, cond_tokens, tree->n_tree, st)) != BR_OK) return s;
+  float* v = v_nodes ? v_nodes : fb.v;
+  for (int i = 0; i < tree->T; ++i) {
+    const int Bi = tree->n_tree * tree->width[i];
+    const SampleMap sm{nullptr, nullptr, tree->n_nodes, tree->off[i], tree->width[i]};
+    for (int b0 = 0; b0 < Bi; b0 += mb) {
+      const int Bc = std::min(mb, Bi - b0);
+      if ((s = fill_sample_maps(fb, sm, b0, Bc, v_nodes != nullptr, st)) != BR_OK) return s;
+      if ((s = forward(model, fb, z_nodes, Bc, sched->t[i], cond_tokens, tree->n_tree, v, st)) != BR_OK) return s;
+    }
+    if ((s = launch_sde_step(tree, sched, seed, i, D, v, v_nodes == nullptr, z_nodes, logp_edges, fb.sde_partials,
+                             st)) != BR_OK)
+      return s;
+  }
+  return BR_OK;
+}
+
+extern "C" br_status br_logprob(const br_tree* tree, const br_model* model, const br_sched* sched,
+                                const void* cond_tokens, const float* z_nodes, const int32_t* edge_ids, int32_t n_edges,
+                                float* logp_out, void* workspace, size_t workspace_bytes, void* stream) {
+  BR_REQUIRE(tree && model && cond_tokens && z_nodes && workspace, BR_EINVAL, "br_logprob: NULL argument");
+  BR_REQUIRE(n_edges >= 0 && (n_edges == 0 || (edge_ids && logp_out)), BR_EINVAL, "br_logprob: bad edge list");
+  br_status s;
+  if ((s = check_sched(tree, sched, "br_logprob")) != BR_OK) return s;
+  if (n_edges == 0) return BR_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const int nn = tree->n_nodes, T = tree->T;
+  const long long total_nodes = (long long)tree->n_tree * nn;
+  BR_REQUIRE(n_edges <= total_nodes, BR_EINVAL, "br_logprob: more edges than the forest has");
+  for (int e = 0; e < n_edges; ++e) {
+    const int g = edge_ids[e];
+    BR_REQUIRE(g >= 0 && g < total_nodes && g % nn != 0, BR_EINVAL, "br_logprob: edge id out of range or a root");
+    BR_REQUIRE(e == 0 || g > edge_ids[e - 1], BR_EINVAL, "br_logprob: edge ids must be strictly ascending");
+  }
+  const int mb = fit_batch(tree, model, max_frontier(tree), workspace_bytes, 0);
+  BR_REQUIRE(mb >= 1, BR_EWORKSPACE, "br_logprob: workspace too small (see br_workspace_bytes)");
+  FwdBuffers fb;
+  const Sizes sz = sizes_for(tree, model, mb);
+  plan_workspace(model, sz.n_cond, mb, sz.v_rows, sz.partial_floats, sz.plan_ints, &fb, workspace);
+
+  // Launch plan: per step, the unique parents (one network evaluation each, shared by
+  // siblings) and for every edge its child row, parent row, velocity row and output slot.
+  struct StepPlan {
+    std::vector<int> rows, cond, crow, prow, vrow, slot;
+    int o_rows, o_cond, o_crow, o_prow, o_vrow, o_slot;
+  };
+  std::vector<StepPlan> sp(T);
+  for (int e = 0; e < n_edges; ++e) {  // ascending ids: parents of one step come out ascending too
+    const int g = edge_ids[e], c = g / nn, n = g - c * nn;
+    const int i = tree->depth[n] - 1, p = c * nn + tree->parent[n];
+    StepPlan& q = sp[i];
+    if (q.rows.empty() || q.rows.back() != p) {
+      q.rows.push_back(p);
+      q.cond.push_back(c);
+    }
+    q.crow.push_back(g);
+    q.prow.push_back(p);
+    q.vrow.push_back((int)q.rows.size() - 1);
+    q.slot.push_back(e);
+  }
+  std::vector<int> host;
+  for (int i = 0; i < T; ++i) {
+    StepPlan& q = sp[i];
+    std::vector<int>* arrs[6] = {&q.rows, &q.cond, &q.crow, &q.prow, &q.vrow, &q.slot};
+    int* offs[6] = {&q.o_rows, &q.o_cond, &q.o_crow, &q.o_prow, &q.o_vrow, &q.o_slot};
+    for (int a = 0; a < 6; ++a) {
+      *offs[a] = (int)host.size();
+      host.insert(host.end(), arrs[a]->begin(), arrs[a]->end());
+    }
+  }
+  BR_REQUIRE((long long)host.size() <= sz.plan_ints, BR_EWORKSPACE, "br_logprob: plan does not fit the workspace");
+  BR_HIP(hipMemcpyAsync(fb.plan, host.data(), host.size() * sizeof(int), hipMemcpyHostToDevice, st));
+  BR_HIP(hipStreamSynchronize(st));
+
+  if ((s = embed_cond(model, fb, cond_tokens, tree->n_tree, st)) != BR_OK) return s;
+  const long long D = model->D;
+  for (int i = 0; i < T; ++i) {
+    const StepPlan& q = sp[i];
+    const int ne = (int)q.crow.size(), np = (int)q.rows.size();
+    if (ne == 0) continue;
+    if (sched->sigma[i] > 0.f) {
+      const SampleMap sm{fb.plan + q.o_rows, fb.plan + q.o_cond, 0, 0, 1};
+      for (int b0 = 0; b0 < np; b0 += mb) {
+        const int Bc = std::min(mb, np - b0);
+        if ((s = fill_sample_maps(fb, sm, b0, Bc, 0, st)) != BR_OK) return s;
+        if ((s = forward(model, fb, z_nodes, Bc, sched->t[i], cond_tokens, tree->n_tree, fb.v, st)) != BR_OK) return s;
+      }
+    }
+    if ((s = launch_logp_eval(sched, i, D, z_nodes, fb.v, fb.plan + q.o_crow, fb.plan + q.o_prow, fb.plan + q.o_vrow,
+                              fb.plan + q.o_slot, ne, logp_out, fb.sde_partials, st)) != BR_OK)
+      return s;
+  }
+  return BR_OK;
+}
+
+extern "C" br_status br_velocity(const br_model* model, const float* z, float t, const void* cond_tokens,
+                                 int32_t n_cond, const int32_t* cond_index, int32_t B, float* v_out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  BR_REQUIRE(model && z && cond_tokens && cond_index && v_out && workspace, BR_EINVAL, "br_velocity: NULL argument");
+  BR_REQUIRE(B >= 1 && n_cond >= 1, BR_EINVAL, "br_velocity: B and n_cond must be >= 1");
+  BR_REQUIRE(std::isfinite(t), BR_EINVAL, "br_velocity: t must be finite");
+  for (int b = 0; b < B; ++b)
+    BR_REQUIRE(cond_index[b] >= 0 && cond_index[b] < n_cond, BR_EINVAL, "br_velocity: cond_index out of range");
+  hipStream_t st = (hipStream_t)stream;
+  // the plan holds cond_index [B]; conditioning buffers are sized for n_cond
+  int lo = 0, hi = B;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) / 2;
+    if (plan_workspace(model, n_cond, mid, 0, 0, B, nullptr, nullptr) <= workspace_bytes) lo = mid;
+    else hi = mid - 1;
+  }
+  const int mb = lo;
+  BR_REQUIRE(mb >= 1, BR_EWORKSPACE, "br_velocity: workspace too small");
+  FwdBuffers fb;
+  plan_workspace(model, n_cond, mb, 0, 0, B, &fb, workspace);
+  BR_HIP(hipMemcpyAsync(fb.plan, cond_index, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
+  BR_HIP(hipStreamSynchronize(st));
+  br_status s;
+  if ((s = embed_cond(model, fb, cond_tokens, n_cond, st)) != BR_OK) return s;
+  const SampleMap sm{nullptr, fb.plan, 0, 0, B};  // row = b
+  for (int b0 = 0; b0 < B; b0 += mb) {
+    const int Bc = std::min(mb, B - b0);
+    if ((s = fill_sample_maps(fb, sm, b0, Bc, 0, st)) != BR_OK) return s;
+    if ((s = forward(model, fb, z, Bc, t, cond_tokens, n_cond, v_out, st)) != BR_OK) return s;
+  }
+  return BR_OK;
+}
+
+extern "C" br_status br_fuse_advantage(const br_tree* tree, const float* leaf_rewards, const float* logp_edges,
+                                       float beta, float eps, int32_t ddof, float a_max, float* rbar_nodes,
+                                       float* adv_nodes, void* stream) {
+  BR_REQUIRE(tree && leaf_rewards && logp_edges && rbar_nodes && adv_nodes, BR_EINVAL, "br_fuse_advantage: NULL argument");
+  BR_REQUIRE(std::isfinite(beta) && std::isfinite(eps) && eps >= 0.f && !std::isnan(a_max), BR_EINVAL,
+             "br_fuse_advantage: beta / eps / a_max out of range");
+  BR_REQUIRE(ddof == 0 || ddof == 1, BR_EINVAL, "br_fuse_advantage: ddof must be 0 or 1");
+  TreeDev td;
+  br_status s;
+  if ((s = tree_device(tree, &td)) != BR_OK) return s;
+  return launch_fuse_advantage(tree, td, leaf_rewards, logp_edges, beta, eps, ddof, a_max, rbar_nodes, adv_nodes,
+                               (hipStream_t)stream);
+}
+
+extern "C" br_status br_prune(const br_tree* tree, const float* leaf_rewards, int32_t width_mode, int32_t b,
+                              const uint8_t* depth_pruned, int32_t* kept_edges, int32_t* n_kept, void* stream) {
+  BR_REQUIRE(tree && leaf_rewards && kept_edges && n_kept, BR_EINVAL, "br_prune: NULL argument");
+  BR_REQUIRE(width_mode >= BR_PRUNE_NONE && width_mode <= BR_PRUNE_EXTREME, BR_EINVAL, "br_prune: unknown width mode");
+  BR_REQUIRE(b >= 0, BR_EINVAL, "br_prune: b must be >= 0");
+  DepthMask dm{};
+  if (depth_pruned)
+    for (int i = 0; i < tree->T; ++i)
+      if (depth_pruned[i]) dm.bits[i >> 5] |= 1u << (i & 31);
+  TreeDev td;
+  br_status s;
+  if ((s = tree_device(tree, &td)) != BR_OK) return s;
+  if (tree->n_nodes == 1) {  // no edges at all (cannot happen with T >= 1, kept for safety)
+    return fail(BR_EINVAL, "br_prune: tree has no edges");
+  }
+  return launch_prune(tree, td, leaf_rewards, width_mode, b, dm, kept_edges, n_kept, (hipStream_t)stream);
+}
+
+extern "C" size_t br_reward_scratch_bytes(const br_tree* tree, int32_t kind, int32_t latent_c, int32_t latent_t,
+                                          int32_t latent_h, int32_t latent_w) {
+  if (!tree || latent_c < 1 || latent_t < 1 || latent_h < 1 || latent_w < 1) return 0;
+  const long long D = (long long)latent_c * latent_t * latent_h * latent_w;
+  return reward_scratch_floats(tree, kind, D, latent_c, latent_t) * sizeof(float);
+}
+
+extern "C" br_status br_leaf_reward(const br_tree* tree, const float* z_nodes, int32_t kind, const float* w, float lam,
+                                    int32_t latent_c, int32_t latent_t, int32_t latent_h, int32_t latent_w,
+                                    float* rewards, void* scratch, size_t scratch_bytes, void* stream) {
+  BR_REQUIRE(tree && z_nodes && w && rewards && scratch, BR_EINVAL, "br_leaf_reward: NULL argument");
+  BR_REQUIRE(kind >= BR_REWARD_LINEAR && kind <= BR_REWARD_VIDEO, BR_EINVAL, "br_leaf_reward: unknown kind");
+  BR_REQUIRE(latent_c >= 1 && latent_t >= 1 && latent_h >= 1 && latent_w >= 1, BR_EINVAL,
+             "br_leaf_reward: latent sizes must be positive");
+  const long long D = (long long)latent_c * latent_t * latent_h * latent_w;
+  BR_REQUIRE(D % 4 == 0, BR_ESHAPE, "br_leaf_reward: latent size must be a multiple of 4");
+  BR_REQUIRE(scratch_bytes >= br_reward_scratch_bytes(tree, kind, latent_c, latent_t, latent_h, latent_w),
+             BR_EWORKSPACE, "br_leaf_reward: scratch too small (see br_reward_scratch_bytes)");
+  return launch_leaf_reward(tree, z_nodes, kind, w, lam, latent_c, latent_t, latent_h, latent_w, rewards,
+                            (float*)scratch, (hipStream_t)stream);
+}
+
+extern "C" br_status br_grpo_objective(const float* logp_new, const float* logp_old_nodes, const float* adv_nodes,
+                                       const int32_t* edge_ids, int32_t n_edges, float clip_eps, float* J,
+                                       void* stream) {
+  BR_REQUIRE(J != nullptr && n_edges >= 0, BR_EINVAL, "br_grpo_objective: J is NULL or n_edges < 0");
+  BR_REQUIRE(n_edges == 0 || (logp_new && logp_old_nodes && adv_nodes && edge_ids), BR_EINVAL,
+             "br_grpo_objective: NULL argument");
+  BR_REQUIRE(std::isfinite(clip_eps) && clip_eps >= 0.f, BR_EINVAL, "br_grpo_objective: clip_eps must be >= 0");
+  return launch_grpo_objective(logp_new, logp_old_nodes, adv_nodes, edge_ids, n_edges, clip_eps, J,
+                               (hipStream_t)stream);
+}
+
+extern "C" size_t br_sde_scratch_bytes(const br_tree* tree, int64_t D) {
+  if (!tree || D < 4) return 0;
+  return (size_t)tree->n_tree * tree->n_leaves * sde_nblk(D) * sizeof(float);
+}
+
+extern "C" br_status br_sde_step(const br_tree* tree, const br_sched* sched, uint64_t seed, int32_t step, int64_t D,
+                                 const float* v_parents, float* z_nodes, float* logp_edges, void* scratch,
+                                 size_t scratch_bytes, void* stream) {
+  BR_REQUIRE(tree && v_parents && z_nodes && logp_edges && scratch, BR_EINVAL, "br_sde_step: NULL argument");
+  br_status s;
+  if ((s = check_sched(tree, sched, "br_sde_step")) != BR_OK) return s;
+  BR_REQUIRE(step >= 0 && step < tree->T, BR_EINVAL, "br_sde_step: step outside [0, T)");
+  BR_REQUIRE(D >= 4 && D % 4 == 0, BR_ESHAPE, "br_sde_step: D must be a positive multiple of 4");
+  BR_REQUIRE(scratch_bytes >= br_sde_scratch_bytes(tree, D), BR_EWORKSPACE, "br_sde_step: scratch too small");
+  return launch_sde_step(tree, sched, seed, step, D, v_parents, 1, z_nodes, logp_edges, (float*)scratch,
+                         (hipStream_t)stream);
+}
+
+extern "C" br_status br_root_noise(const br_tree* tree, uint64_t seed, const int32_t* noise_group, int64_t D,
+                                   float* z_nodes, void* stream) {
+  BR_REQUIRE(tree && noise_group && z_nodes, BR_EINVAL, "br_root_noise: NULL argument");
+  BR_REQUIRE(D >= 4 && D % 4 == 0, BR_ESHAPE, "br_root_noise: D must be a positive multiple of 4");
+  return launch_root_noise(tree, seed, noise_group, D, z_nodes, (hipStream_t)stream);
+}
+
+extern "C" br_status br_noise_stream(uint64_t seed, uint32_t node_id, uint32_t step, uint32_t tag, int64_t n_quads,
+                                     uint32_t* words, float* normals, void* stream) {
+  BR_REQUIRE(n_quads >= 0 && n_quads <= 0xFFFFFFFFLL, BR_EINVAL, "br_noise_stream: n_quads out of range");
+  BR_REQUIRE(words || normals, BR_EINVAL, "br_noise_stream: both outputs are NULL");
+  return launch_noise_stream(seed, node_id, step, tag, n_quads, words, normals, (hipStream_t)stream);
+}

@@ -1,0 +1,170 @@
+// bf16 flash attention on the gfx950 matrix cores: softmax(Q K^T / sqrt(d)) V over
+// all L tokens of a sample, one workgroup per (128 queries, head, sample), four
+// wavefronts of 32 queries each, key/value tiles of 64 staged through LDS.
+//
+// Scores are computed transposed, S^T = K Q^T: in the 32x32 MFMA accumulator a
+// lane then holds 16 keys of ONE query (the other 16 sit in lane ^ 32), so the
+// running max / sum / rescale of the online softmax are per-lane scalars and the
+// exponentiated tile is already laid out as the column operand of O^T = V^T P^T.
+// The contraction order of that product is permuted to match the accumulator
+// layout; V is staged transposed ([d][key]) so the row operand is two 8-byte reads.
+#include "common.h"
+#include "dit.h"
+
+namespace br {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int KV_TILE = 64;
+constexpr int VT_STRIDE = 68;  // bf16 elements per row of the transposed V tile (136 B)
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
+                                                        int H, float scale_log2) {
+  constexpr int CH = DH / 8;    // 16-byte chunks per K row
+  constexpr int KS = DH / 16;   // MFMA k-steps of the score product
+  constexpr int DB = DH / 32;   // 32-row blocks of O^T
+  __shared__ __attribute__((aligned(16))) uint4 sK[KV_TILE * CH];
+  __shared__ __attribute__((aligned(16))) bf16 sVt[DH * VT_STRIDE];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const size_t ld = (size_t)3 * H;
+  const bf16* base = qkv + (size_t)b * L * ld + (size_t)h * DH;
+  const int qi = blockIdx.x * 128 + wv * 32 + l32;
+  const int qc = min(qi, L - 1);
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks] = *reinterpret_cast<const bf16x8*>(base + (size_t)qc * ld + ks * 16 + lh * 8);
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int nkv = (L + KV_TILE - 1) / KV_TILE;
+  for (int it = 0; it < nkv; ++it) {
+    const int k0 = it * KV_TILE;
+    __syncthreads();
+    // K tile: row-major, chunk c of row r in slot c ^ (r & 7)
+#pragma unroll
+    for (int i = 0; i < KV_TILE * CH / 256; ++i) {
+      const int id = tid + i * 256, row = id / CH, c = id % CH;
+      const int key = min(k0 + row, L - 1);
+      sK[row * CH + (c ^ (row & 7))] = *reinterpret_cast<const uint4*>(base + (size_t)key * ld + H + c * 8);
+    }
+    // V tile transposed: a thread takes two neighbouring keys and one 8-wide d
+    // chunk and writes eight (key pair) words
+#pragma unroll
+    for (int i = 0; i < 32 * CH / 256; ++i) {
+      const int id = tid + i * 256, p = id & 31, c = id >> 5;
+      const int ka = min(k0 + 2 * p, L - 1), kb = min(k0 + 2 * p + 1, L - 1);
+      const bf16x8 va = *reinterpret_cast<const bf16x8*>(base + (size_t)ka * ld + 2 * H + c * 8);
+      const bf16x8 vb = *reinterpret_cast<const bf16x8*>(base + (size_t)kb * ld + 2 * H + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 pr = {va[e], vb[e]};
+        *reinterpret_cast<bf16x2*>(&sVt[(c * 8 + e) * VT_STRIDE + 2 * p]) = pr;
+      }
+    }
+    __syncthreads();
+
+    // S^T tile: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query l32
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      const int row = kb * 32 + l32;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int c = ks * 2 + lh;
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[row * CH + (c ^ (row & 7))]);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+      }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        const float v = key < L ? s[kb][r] * scale_log2 : -INFINITY;
+        s[kb][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_new);
+        s[kb][r] = p;
+        psum += p;
+      }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+
+    // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[kb][8 * j + e];
+        const int kofs = kb * 32 + j * 16 + lh * 4;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          const bf16* vr = &sVt[(d * 32 + l32) * VT_STRIDE + kofs];
+          const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vr);
+          const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vr + 8);
+          const bf16x8 vf = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+        }
+      }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.f / l_tot;
+  if (qi < L) {
+    bf16* orow = out + ((size_t)b * L + qi) * H + (size_t)h * DH;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v = {(bf16)(o[d][4 * g] * inv), (bf16)(o[d][4 * g + 1] * inv), (bf16)(o[d][4 * g + 2] * inv),
+                    (bf16)(o[d][4 * g + 3] * inv)};
+        *reinterpret_cast<bf16x4*>(orow + d * 32 + g * 8 + lh * 4) = v;
+      }
+  }
+}
+
+br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st) {
+  BR_REQUIRE(NH <= 65535 && B <= 65535, BR_ESHAPE, "attention: too many heads or samples for one launch");
+  BR_REQUIRE(L >= 1, BR_EINVAL, "attention: empty sequence");
+  dim3 g(cdiv(L, 128), NH, B), blk(256);
+  const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)DH));
+  const int H = NH * DH;
+  if (DH == 64) hipLaunchKernelGGL((attn_bf16_kernel<64>), g, blk, 0, st, qkv, out, L, H, scale_log2);
+  else if (DH == 128) hipLaunchKernelGGL((attn_bf16_kernel<128>), g, blk, 0, st, qkv, out, L, H, scale_log2);
+  else return fail(BR_ESHAPE, "bf16 attention: head dim must be 64 or 128");
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+}  // namespace br

@@ -1,0 +1,165 @@
+// Velocity-network internals: model handle, workspace plan, epilogues, launchers.
+#pragma once
+#include "common.h"
+
+typedef __bf16 bf16;
+
+struct br_model {
+  br_model_cfg cfg;
+  const void* w[BR_W_COUNT];
+  // derived
+  int H, NB, NH, DH, R, n_img, pd, L, Nc, cd, A;  // A = NB*6H + 2H
+  long long D;
+  int gt, gh, gw;
+};
+
+namespace br {
+
+// ---- epilogues of the GEMMs (fused bias / activation / gate / residual / scatter)
+enum EpiMode {
+  EPI_BIAS = 0,           // out[m, n] = acc + bias[n]                        (T out)
+  EPI_BIAS_GELU = 1,      // out[m, n] = gelu_tanh(acc + bias[n])             (T out)
+  EPI_BIAS_GATE_RES = 2,  // x[m, n] += gate[cond(m / L)][n] * (acc + bias)   (fp32 in place)
+  EPI_PATCH_EMBED = 3,    // x[(m / n_img) L + m % n_img, n] = acc + bias + pos[m % n_img, n]
+  EPI_BIAS_F32 = 4,       // out[m, n] = acc + bias[n]                        (fp32 out)
+  EPI_UNPATCH = 5         // v[vrow(m / n_img)][latent index of (m % n_img, n)] = acc + bias
+};
+
+struct EpiArgs {
+  const float* bias;
+  void* out;
+  int ldo;
+  // gate / residual
+  const float* mods;   // [n_cond, A]
+  int A, gate_off;
+  const int* condmap;  // [B]
+  int L, n_img;
+  const float* pos;    // [n_img, H]
+  // unpatchify
+  const int* vrows;    // [B] destination row of each sample in v
+  long long D;
+  int lt, lh, lw, pt, ph, pw, gh, gw;
+};
+
+struct FwdBuffers {  // carved from the workspace
+  int* rowmap;
+  int* condmap;
+  int* vrows;
+  float *temb, *h1, *ct, *pooled, *cvec, *mods, *cond_emb, *x, *sde_partials;
+  void *patches, *xn, *qkv, *hid;
+  float* v;       // compact velocity [max_frontier, D] (rollout only)
+  int* plan;      // br_logprob launch plan
+  size_t total;
+};
+
+size_t plan_workspace(const br_model* m, int n_cond, int max_batch, long long v_rows, long long partial_floats,
+                      long long plan_ints, FwdBuffers* fb, void* base);
+
+// One network evaluation of `B` samples (B <= max_batch of the plan).
+// z_base: latent rows; smap: sample -> (row, cond); v_out rows given by fb.vrows.
+br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, float t,
+                  const void* cond_tokens, int n_cond, float* v_out, hipStream_t st);
+// Fill rowmap/condmap/vrows for a batch [b0, b0+B) of a frontier.
+br_status fill_sample_maps(const FwdBuffers& fb, const SampleMap& smap, int b0, int B, int v_mode_rows, hipStream_t st);
+// Condition-token embedding, once per call.
+br_status embed_cond(const br_model* m, const FwdBuffers& fb, const void* cond_tokens, int n_cond, hipStream_t st);
+
+// ---- op launchers (dit_kernels.hip, gemm_bf16.hip, attn_bf16.hip)
+br_status launch_gemm(int dtype, int mode, const void* A, int lda, const void* W, int ldw, int M, int N, int K,
+                      const EpiArgs& ea, hipStream_t st);
+br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, int NH, int DH, hipStream_t st);
+br_status launch_gemm_bf16(int mode, const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K,
+                           const EpiArgs& ea, int variant, hipStream_t st);
+br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st);
+br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, int rows_per_sample, int L_in, int H,
+                             const float* mods, int A, int shift_off, int scale_off, const int* condmap,
+                             hipStream_t st);
+
+// ---- epilogue device code, shared by the fp32 and the MFMA GEMM
+__device__ inline float gelu_tanh_f(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  // tanh(u) = 1 - 2 / (exp(2u) + 1)
+  const float e = __expf(2.f * u);
+  const float th = 1.f - 2.f / (e + 1.f);
+  return 0.5f * x * (1.f + th);
+}
+
+template <typename T>
+__device__ inline void store4(T* p, float a, float b, float c, float d);
+template <>
+__device__ inline void store4<float>(float* p, float a, float b, float c, float d) {
+  *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+template <>
+__device__ inline void store4<bf16>(bf16* p, float a, float b, float c, float d) {
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 v = {(bf16)a, (bf16)b, (bf16)c, (bf16)d};
+  *reinterpret_cast<bf16x4*>(p) = v;
+}
+
+template <int MODE, typename T>
+struct Epilogue {
+  EpiArgs a;
+  struct Row {
+    long long o;       // element offset of the output row
+    const float* aux;  // gate row / pos row
+    int tok;
+  };
+  __device__ inline Row row(int m) const {
+    Row r;
+    r.aux = nullptr;
+    r.tok = 0;
+    if (MODE == EPI_BIAS_GATE_RES) {
+      r.o = (long long)m * a.ldo;
+      r.aux = a.mods + (size_t)a.condmap[m / a.L] * a.A + a.gate_off;
+    } else if (MODE == EPI_PATCH_EMBED) {
+      const int b = m / a.n_img, tok = m - b * a.n_img;
+      r.o = ((long long)b * a.L + tok) * a.ldo;
+      r.aux = a.pos + (size_t)tok * a.ldo;
+    } else if (MODE == EPI_UNPATCH) {
+      const int b = m / a.n_img;
+      r.tok = m - b * a.n_img;
+      r.o = (long long)a.vrows[b] * a.D;
+    } else {
+      r.o = (long long)m * a.ldo;
+    }
+    return r;
+  }
+  // four consecutive output columns n..n+3 (n % 4 == 0)
+  __device__ inline void store(const Row& r, int n, float v0, float v1, float v2, float v3) const {
+    const float4 bb = *reinterpret_cast<const float4*>(a.bias + n);
+    v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
+    if (MODE == EPI_BIAS) {
+      store4<T>(reinterpret_cast<T*>(a.out) + r.o + n, v0, v1, v2, v3);
+    } else if (MODE == EPI_BIAS_GELU) {
+      store4<T>(reinterpret_cast<T*>(a.out) + r.o + n, gelu_tanh_f(v0), gelu_tanh_f(v1), gelu_tanh_f(v2),
+                gelu_tanh_f(v3));
+    } else if (MODE == EPI_BIAS_GATE_RES) {
+      float* x = reinterpret_cast<float*>(a.out) + r.o + n;
+      const float4 g = *reinterpret_cast<const float4*>(r.aux + n);
+      float4 xv = *reinterpret_cast<float4*>(x);
+      xv.x = fmaf(g.x, v0, xv.x); xv.y = fmaf(g.y, v1, xv.y); xv.z = fmaf(g.z, v2, xv.z); xv.w = fmaf(g.w, v3, xv.w);
+      *reinterpret_cast<float4*>(x) = xv;
+    } else if (MODE == EPI_PATCH_EMBED) {
+      const float4 p = *reinterpret_cast<const float4*>(r.aux + n);
+      store4<float>(reinterpret_cast<float*>(a.out) + r.o + n, v0 + p.x, v1 + p.y, v2 + p.z, v3 + p.w);
+    } else if (MODE == EPI_BIAS_F32) {
+      store4<float>(reinterpret_cast<float*>(a.out) + r.o + n, v0, v1, v2, v3);
+    } else {  // EPI_UNPATCH: token (tt, th, tw) raster, element (c, dt, dh, dw)
+      float* v = reinterpret_cast<float*>(a.out) + r.o;
+      const int tw = r.tok % a.gw, th = (r.tok / a.gw) % a.gh, tt = r.tok / (a.gw * a.gh);
+      const float vals[4] = {v0, v1, v2, v3};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int el = n + e;
+        const int dw = el % a.pw, dh = (el / a.pw) % a.ph, dt = (el / (a.pw * a.ph)) % a.pt,
+                  c = el / (a.pw * a.ph * a.pt);
+        const long long idx =
+            (((long long)c * a.lt + tt * a.pt + dt) * a.lh + th * a.ph + dh) * a.lw + tw * a.pw + dw;
+        v[idx] = vals[e];
+      }
+    }
+  }
+};
+
+}  // namespace br

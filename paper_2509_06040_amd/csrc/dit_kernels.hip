@@ -1,0 +1,389 @@
+// Velocity network: the memory-bound and small kernels (sample maps, patchify,
+// condition broadcast, conditioning path, LayerNorm-modulate) and the fp32 GEMM /
+// attention used by BR_F32 models.  The bf16 MFMA GEMM and flash attention live in
+// gemm_bf16.hip and attn_bf16.hip.
+#include "common.h"
+#include "dit.h"
+
+namespace br {
+
+template <typename T>
+__device__ inline float to_f(T v) { return (float)v; }
+
+// ------------------------------------------------------------- sample maps
+__global__ void sample_map_kernel(SampleMap sm, int b0, int B, int v_rows_mode, int* __restrict__ rowmap,
+                                  int* __restrict__ condmap, int* __restrict__ vrows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B) return;
+  const int b = b0 + i;
+  const int row = sm.rows ? sm.rows[b] : (b / sm.width) * sm.n_nodes + sm.off + b % sm.width;
+  rowmap[i] = row;
+  condmap[i] = sm.cond ? sm.cond[b] : b / sm.width;
+  vrows[i] = v_rows_mode ? row : b;
+}
+
+// ---------------------------------------------------------------- patchify
+// patches[(b n_img + tok) pd + el] = z[rowmap[b]][latent index]; tokens in (t,h,w)
+// raster order, patch vector in (c, dt, dh, dw) order.
+template <typename T>
+__global__ __launch_bounds__(256) void patchify_kernel(const float* __restrict__ z, const int* __restrict__ rowmap,
+                                                       long long D, int n_img, int pd, int lt, int lh, int lw, int pt,
+                                                       int ph, int pw, int gh, int gw, long long total,
+                                                       T* __restrict__ out) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const int el = (int)(i % pd);
+    const long long bt = i / pd;
+    const int tok = (int)(bt % n_img), b = (int)(bt / n_img);
+    const int tw = tok % gw, th = (tok / gw) % gh, tt = tok / (gw * gh);
+    const int dw = el % pw, dh = (el / pw) % ph, dt = (el / (pw * ph)) % pt, c = el / (pw * ph * pt);
+    const long long idx = (((long long)c * lt + tt * pt + dt) * lh + th * ph + dh) * lw + tw * pw + dw;
+    out[i] = (T)z[(size_t)rowmap[b] * D + idx];
+  }
+}
+
+// x[b, n_img + j, :] = cond_emb[condmap[b], j, :]
+__global__ __launch_bounds__(256) void cond_broadcast_kernel(const float* __restrict__ cond_emb,
+                                                             const int* __restrict__ condmap, int L, int n_img, int Nc,
+                                                             int H, long long total4, float* __restrict__ x) {
+  const int H4 = H >> 2;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total4; i += (long long)gridDim.x * 256) {
+    const int h4 = (int)(i % H4);
+    const long long bj = i / H4;
+    const int j = (int)(bj % Nc), b = (int)(bj / Nc);
+    const float4 v = reinterpret_cast<const float4*>(cond_emb)[((size_t)condmap[b] * Nc + j) * H4 + h4];
+    reinterpret_cast<float4*>(x)[((size_t)b * L + n_img + j) * H4 + h4] = v;
+  }
+}
+
+// ------------------------------------------------------- conditioning path
+// temb = [cos(1000 t f_k), sin(1000 t f_k)], f_k = 10000^(-k/128); pooled = mean of
+// the condition tokens.  Angles in fp64: 1000 t f is too large for fp32 sin/cos.
+template <typename T>
+__global__ __launch_bounds__(256) void temb_pool_kernel(float t, const T* __restrict__ cond, int n_cond, int Nc, int cd,
+                                                        float* __restrict__ temb, float* __restrict__ pooled) {
+  if (blockIdx.x == 0) {
+    for (int k = threadIdx.x; k < 128; k += 256) {
+      const double f = exp(-log(10000.0) * (double)k / 128.0);
+      const double a = 1000.0 * (double)t * f;
+      temb[k] = (float)cos(a);
+      temb[128 + k] = (float)sin(a);
+    }
+    return;
+  }
+  const int c = blockIdx.x - 1;
+  for (int d = threadIdx.x; d < cd; d += 256) {
+    float s = 0.f;
+    for (int j = 0; j < Nc; ++j) s += to_f(cond[((size_t)c * Nc + j) * cd + d]);
+    pooled[(size_t)c * cd + d] = s / (float)Nc;
+  }
+}
+
+__device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
+
+// out[r, n] = post( sum_k pre(in[r, k]) W[n, k] + bias[n] + add[n] ), r < R <= 8.
+// Weight-streaming: one wavefront per output column, lanes along k.
+template <typename TW, int R>
+__global__ __launch_bounds__(256) void skinny_gemm_kernel(const float* __restrict__ in, int ldi,
+                                                          const TW* __restrict__ W, int K, int N,
+                                                          const float* __restrict__ bias,
+                                                          const float* __restrict__ add, int pre_silu, int post_silu,
+                                                          float* __restrict__ out, int ldo) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  const TW* wr = W + (size_t)n * K;
+  for (int k = lane; k < K; k += 64) {
+    const float w = to_f(wr[k]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float a = in[(size_t)r * ldi + k];
+      if (pre_silu) a = silu_f(a);
+      acc[r] = fmaf(a, w, acc[r]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    float s = acc[r];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+    if (lane == 0) {
+      s += bias[n] + (add ? add[n] : 0.f);
+      out[(size_t)r * ldo + n] = post_silu ? silu_f(s) : s;
+    }
+  }
+}
+
+template <typename TW>
+static br_status skinny(const float* in, int ldi, int R, const TW* W, int K, int N, const float* bias, const float* add,
+                        int pre, int post, float* out, int ldo, hipStream_t st) {
+  for (int r0 = 0; r0 < R; r0 += 8) {
+    const int r = std::min(8, R - r0);
+    const float* ip = in + (size_t)r0 * ldi;
+    float* op = out + (size_t)r0 * ldo;
+    dim3 g(cdiv(N, 4)), b(256);
+#define BR_SK(RR) hipLaunchKernelGGL((skinny_gemm_kernel<TW, RR>), g, b, 0, st, ip, ldi, W, K, N, bias, add, pre, post, op, ldo)
+    switch (r) {
+      case 1: BR_SK(1); break;
+      case 2: BR_SK(2); break;
+      case 3: BR_SK(3); break;
+      case 4: BR_SK(4); break;
+      case 5: BR_SK(5); break;
+      case 6: BR_SK(6); break;
+      case 7: BR_SK(7); break;
+      default: BR_SK(8); break;
+    }
+#undef BR_SK
+    BR_LAUNCH_CHECK();
+  }
+  return BR_OK;
+}
+
+// cvec = t_mlp(temb) + pool_lin(pooled); mods = ada_lin(silu(cvec))
+template <typename T>
+static br_status conditioning_t(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond,
+                                hipStream_t st) {
+  const int H = m->H;
+  hipLaunchKernelGGL((temb_pool_kernel<T>), dim3(1 + n_cond), dim3(256), 0, st, t, (const T*)cond, n_cond, m->Nc, m->cd,
+                     fb.temb, fb.pooled);
+  BR_LAUNCH_CHECK();
+  br_status s;
+  if ((s = skinny<T>(fb.temb, 256, 1, (const T*)m->w[BR_W_T1_W], 256, H, (const float*)m->w[BR_W_T1_B], nullptr, 0, 1,
+                     fb.h1, H, st)) != BR_OK) return s;
+  if ((s = skinny<T>(fb.h1, H, 1, (const T*)m->w[BR_W_T2_W], H, H, (const float*)m->w[BR_W_T2_B], nullptr, 0, 0, fb.ct,
+                     H, st)) != BR_OK) return s;
+  if ((s = skinny<T>(fb.pooled, m->cd, n_cond, (const T*)m->w[BR_W_POOL_W], m->cd, H, (const float*)m->w[BR_W_POOL_B],
+                     fb.ct, 0, 1, fb.cvec, H, st)) != BR_OK) return s;  // cvec holds silu(cvec)
+  return skinny<T>(fb.cvec, H, n_cond, (const T*)m->w[BR_W_ADA_W], H, m->A, (const float*)m->w[BR_W_ADA_B], nullptr, 0,
+                   0, fb.mods, m->A, st);
+}
+
+br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st) {
+  return m->cfg.dtype == BR_BF16 ? conditioning_t<bf16>(m, fb, t, cond, n_cond, st)
+                                 : conditioning_t<float>(m, fb, t, cond, n_cond, st);
+}
+
+// ------------------------------------------------------- LayerNorm-modulate
+// out[r, :] = LN(x[src(r), :]) (1 + scale) + shift; one wavefront per row.
+// r = b * rows_per_sample + tok, src = b * L_in + tok; LN without affine, eps 1e-6.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restrict__ x, T* __restrict__ out, int n_rows,
+                                                          int rows_per_sample, int L_in, int H,
+                                                          const float* __restrict__ mods, int A, int shift_off,
+                                                          int scale_off, const int* __restrict__ condmap) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  const int b = r / rows_per_sample, tok = r - b * rows_per_sample;
+  const float4* xr = reinterpret_cast<const float4*>(x + ((size_t)b * L_in + tok) * H);
+  const int H4 = H >> 2;
+  float s = 0.f;
+  for (int i = lane; i < H4; i += 64) {
+    const float4 v = xr[i];
+    s += (v.x + v.y) + (v.z + v.w);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  const float mean = s / (float)H;
+  float q = 0.f;
+  for (int i = lane; i < H4; i += 64) {
+    const float4 v = xr[i];
+    const float a = v.x - mean, bq = v.y - mean, c = v.z - mean, d = v.w - mean;
+    q += (a * a + bq * bq) + (c * c + d * d);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+  const float rstd = 1.0f / __builtin_sqrtf(q / (float)H + 1e-6f);
+  const float* mrow = mods + (size_t)condmap[b] * A;
+  const float4* sh = reinterpret_cast<const float4*>(mrow + shift_off);
+  const float4* sc = reinterpret_cast<const float4*>(mrow + scale_off);
+  T* orow = out + (size_t)r * H;
+  for (int i = lane; i < H4; i += 64) {
+    const float4 v = xr[i], a = sh[i], g = sc[i];
+    store4<T>(orow + 4 * i, fmaf((v.x - mean) * rstd, 1.f + g.x, a.x), fmaf((v.y - mean) * rstd, 1.f + g.y, a.y),
+              fmaf((v.z - mean) * rstd, 1.f + g.z, a.z), fmaf((v.w - mean) * rstd, 1.f + g.w, a.w));
+  }
+}
+
+br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, int rows_per_sample, int L_in, int H,
+                             const float* mods, int A, int shift_off, int scale_off, const int* condmap,
+                             hipStream_t st) {
+  if (n_rows == 0) return BR_OK;
+  dim3 g(cdiv(n_rows, 4)), b(256);
+  if (dtype == BR_BF16)
+    hipLaunchKernelGGL((ln_modulate_kernel<bf16>), g, b, 0, st, x, (bf16*)out, n_rows, rows_per_sample, L_in, H, mods, A,
+                       shift_off, scale_off, condmap);
+  else
+    hipLaunchKernelGGL((ln_modulate_kernel<float>), g, b, 0, st, x, (float*)out, n_rows, rows_per_sample, L_in, H, mods,
+                       A, shift_off, scale_off, condmap);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+// --------------------------------------------------------------- fp32 GEMM
+// C[m, n] = sum_k A[m, k] W[n, k]; 64x64 tile, 16-deep, 4x4 outputs per thread.
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, int lda, const float* __restrict__ W,
+                                                       int ldw, int M, int N, int K, Epilogue<MODE, float> epi) {
+  __shared__ float sA[16][64 + 4], sW[16][64 + 4];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + i * 256, row = e >> 4, kk = e & 15;
+      const int gm = m0 + row, gn = n0 + row, gk = k0 + kk;
+      sA[kk][row] = (gm < M && gk < K) ? A[(size_t)gm * lda + gk] : 0.f;
+      sW[kk][row] = (gn < N && gk < K) ? W[(size_t)gn * ldw + gk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = sA[kk][ty * 4 + i];
+        w[i] = sW[kk][tx * 4 + i];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  const int n = n0 + tx * 4;
+  if (n >= N) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m < M) {
+      const auto r = epi.row(m);
+      epi.store(r, n, acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+    }
+  }
+}
+
+template <int MODE>
+static br_status gemm_f32_mode(const float* A, int lda, const float* W, int ldw, int M, int N, int K, const EpiArgs& ea,
+                               hipStream_t st) {
+  Epilogue<MODE, float> epi{ea};
+  hipLaunchKernelGGL((gemm_f32_kernel<MODE>), dim3(cdiv(N, 64), cdiv(M, 64)), dim3(256), 0, st, A, lda, W, ldw, M, N, K,
+                     epi);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+br_status launch_gemm(int dtype, int mode, const void* A, int lda, const void* W, int ldw, int M, int N, int K,
+                      const EpiArgs& ea, hipStream_t st) {
+  if (M == 0) return BR_OK;
+  BR_REQUIRE(N % 4 == 0, BR_ESHAPE, "gemm: N must be a multiple of 4");
+  if (dtype == BR_BF16)
+    return launch_gemm_bf16(mode, (const bf16*)A, lda, (const bf16*)W, ldw, M, N, K, ea, -1, st);
+  const float* a = (const float*)A;
+  const float* w = (const float*)W;
+  switch (mode) {
+    case EPI_BIAS: return gemm_f32_mode<EPI_BIAS>(a, lda, w, ldw, M, N, K, ea, st);
+    case EPI_BIAS_GELU: return gemm_f32_mode<EPI_BIAS_GELU>(a, lda, w, ldw, M, N, K, ea, st);
+    case EPI_BIAS_GATE_RES: return gemm_f32_mode<EPI_BIAS_GATE_RES>(a, lda, w, ldw, M, N, K, ea, st);
+    case EPI_PATCH_EMBED: return gemm_f32_mode<EPI_PATCH_EMBED>(a, lda, w, ldw, M, N, K, ea, st);
+    case EPI_BIAS_F32: return gemm_f32_mode<EPI_BIAS_F32>(a, lda, w, ldw, M, N, K, ea, st);
+    case EPI_UNPATCH: return gemm_f32_mode<EPI_UNPATCH>(a, lda, w, ldw, M, N, K, ea, st);
+  }
+  return fail(BR_EINVAL, "gemm: unknown epilogue");
+}
+
+// ---------------------------------------------------------- fp32 attention
+// One thread per query, streaming over all keys with an online softmax.
+template <int DH>
+__global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ qkv, float* __restrict__ out, int L,
+                                                      int H, float scale) {
+  const int b = blockIdx.z, h = blockIdx.y, qi = blockIdx.x * 64 + threadIdx.x;
+  const float* base = qkv + (size_t)b * L * 3 * H + h * DH;
+  const bool live = qi < L;
+  float q[DH], o[DH];
+#pragma unroll
+  for (int d = 0; d < DH; ++d) {
+    q[d] = live ? base[(size_t)qi * 3 * H + d] * scale : 0.f;
+    o[d] = 0.f;
+  }
+  float mx = -INFINITY, den = 0.f;
+  for (int j = 0; j < L; ++j) {
+    const float* kr = base + (size_t)j * 3 * H + H;
+    const float* vr = kr + H;
+    float s = 0.f;
+#pragma unroll
+    for (int d = 0; d < DH; ++d) s = fmaf(q[d], kr[d], s);
+    const float mn = fmaxf(mx, s);
+    const float alpha = __expf(mx - mn), p = __expf(s - mn);
+    den = den * alpha + p;
+#pragma unroll
+    for (int d = 0; d < DH; ++d) o[d] = fmaf(p, vr[d], o[d] * alpha);
+    mx = mn;
+  }
+  if (live) {
+    float* orow = out + ((size_t)b * L + qi) * H + h * DH;
+    const float inv = 1.f / den;
+#pragma unroll
+    for (int d = 0; d < DH; ++d) orow[d] = o[d] * inv;
+  }
+}
+
+br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, int NH, int DH, hipStream_t st) {
+  if (B == 0) return BR_OK;
+  if (dtype == BR_BF16) return launch_attention_bf16((const bf16*)qkv, (bf16*)out, B, L, NH, DH, st);
+  BR_REQUIRE(NH <= 65535 && B <= 65535, BR_ESHAPE, "attention: too many heads or samples for one launch");
+  dim3 g(cdiv(L, 64), NH, B), blk(64);
+  const float scale = 1.0f / sqrtf((float)DH);
+  const int H = NH * DH;
+#define BR_AT(D_) hipLaunchKernelGGL((attn_f32_kernel<D_>), g, blk, 0, st, (const float*)qkv, (float*)out, L, H, scale)
+  switch (DH) {
+    case 16: BR_AT(16); break;
+    case 32: BR_AT(32); break;
+    case 64: BR_AT(64); break;
+    case 128: BR_AT(128); break;
+    default: return fail(BR_ESHAPE, "attention: head dim must be 16, 32, 64 or 128");
+  }
+#undef BR_AT
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+// -------------------------------------------------------------- launchers
+br_status fill_sample_maps(const FwdBuffers& fb, const SampleMap& smap, int b0, int B, int v_mode_rows, hipStream_t st) {
+  hipLaunchKernelGGL(sample_map_kernel, dim3(cdiv(B, 256)), dim3(256), 0, st, smap, b0, B, v_mode_rows, fb.rowmap,
+                     fb.condmap, fb.vrows);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+br_status launch_patchify(const br_model* m, const FwdBuffers& fb, const float* z, int B, hipStream_t st) {
+  const long long total = (long long)B * m->n_img * m->pd;
+  const int nb = (int)std::min<long long>((total + 255) / 256, 65535 * 16);
+  const br_model_cfg& c = m->cfg;
+  if (c.dtype == BR_BF16)
+    hipLaunchKernelGGL((patchify_kernel<bf16>), dim3(nb), dim3(256), 0, st, z, fb.rowmap, m->D, m->n_img, m->pd,
+                       c.latent_t, c.latent_h, c.latent_w, c.patch_t, c.patch_h, c.patch_w, m->gh, m->gw, total,
+                       (bf16*)fb.patches);
+  else
+    hipLaunchKernelGGL((patchify_kernel<float>), dim3(nb), dim3(256), 0, st, z, fb.rowmap, m->D, m->n_img, m->pd,
+                       c.latent_t, c.latent_h, c.latent_w, c.patch_t, c.patch_h, c.patch_w, m->gh, m->gw, total,
+                       (float*)fb.patches);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+br_status launch_cond_broadcast(const br_model* m, const FwdBuffers& fb, int B, hipStream_t st) {
+  const long long total4 = (long long)B * m->Nc * (m->H / 4);
+  if (total4 == 0) return BR_OK;
+  const int nb = (int)std::min<long long>((total4 + 255) / 256, 65535 * 16);
+  hipLaunchKernelGGL(cond_broadcast_kernel, dim3(nb), dim3(256), 0, st, fb.cond_emb, fb.condmap, m->L, m->n_img, m->Nc,
+                     m->H, total4, fb.x);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+}  // namespace br

@@ -1,0 +1,194 @@
+// Model handle, workspace plan and one evaluation of the velocity network.
+#include <new>
+
+#include "common.h"
+#include "dit.h"
+#include "kernels.h"
+
+namespace br {
+br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st);
+br_status launch_patchify(const br_model* m, const FwdBuffers& fb, const float* z, int B, hipStream_t st);
+br_status launch_cond_broadcast(const br_model* m, const FwdBuffers& fb, int B, hipStream_t st);
+
+static size_t esize(const br_model* m) { return m->cfg.dtype == BR_BF16 ? 2 : 4; }
+
+size_t plan_workspace(const br_model* m, int n_cond, int max_batch, long long v_rows, long long partial_floats,
+                      long long plan_ints, FwdBuffers* fb, void* base) {
+  size_t o = 0;
+  char* p = reinterpret_cast<char*>(base);
+  auto take = [&](size_t bytes) {
+    void* r = p ? p + o : nullptr;
+    o += align_up(bytes ? bytes : 1, 256);
+    return r;
+  };
+  const size_t B = (size_t)max_batch, H = m->H, L = m->L, es = esize(m);
+  FwdBuffers f;
+  f.rowmap = (int*)take(B * 4);
+  f.condmap = (int*)take(B * 4);
+  f.vrows = (int*)take(B * 4);
+  f.temb = (float*)take(256 * 4);
+  f.h1 = (float*)take(H * 4);
+  f.ct = (float*)take(H * 4);
+  f.pooled = (float*)take((size_t)n_cond * m->cd * 4);
+  f.cvec = (float*)take((size_t)n_cond * H * 4);
+  f.mods = (float*)take((size_t)n_cond * m->A * 4);
+  f.cond_emb = (float*)take((size_t)n_cond * m->Nc * H * 4);
+  f.x = (float*)take(B * L * H * 4);
+  f.patches = take(B * m->n_img * m->pd * es);
+  f.xn = take(B * L * H * es);
+  f.qkv = take(B * L * 3 * H * es);
+  f.hid = take(B * L * (size_t)m->R * H * es);
+  f.v = (float*)take((size_t)v_rows * m->D * 4);
+  f.sde_partials = (float*)take((size_t)partial_floats * 4);
+  f.plan = (int*)take((size_t)plan_ints * 4);
+  f.total = o;
+  if (fb) *fb = f;
+  return o;
+}
+
+br_status embed_cond(const br_model* m, const FwdBuffers& fb, const void* cond_tokens, int n_cond, hipStream_t st) {
+  if (m->Nc == 0) return BR_OK;
+  EpiArgs ea{};
+  ea.bias = (const float*)m->w[BR_W_COND_B];
+  ea.out = fb.cond_emb;
+  ea.ldo = m->H;
+  return launch_gemm(m->cfg.dtype, EPI_BIAS_F32, cond_tokens, m->cd, m->w[BR_W_COND_W], m->cd, n_cond * m->Nc, m->H,
+                     m->cd, ea, st);
+}
+
+br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, float t, const void* cond_tokens,
+                  int n_cond, float* v_out, hipStream_t st) {
+  const int H = m->H, L = m->L, dt = m->cfg.dtype;
+  const size_t es = esize(m);
+  br_status s;
+#define BR_TRY(x) do { if ((s = (x)) != BR_OK) return s; } while (0)
+  BR_TRY(conditioning(m, fb, t, cond_tokens, n_cond, st));
+  BR_TRY(launch_patchify(m, fb, z_base, B, st));
+  {
+    EpiArgs ea{};
+    ea.bias = (const float*)m->w[BR_W_PATCH_B];
+    ea.out = fb.x;
+    ea.ldo = H;
+    ea.L = L;
+    ea.n_img = m->n_img;
+    ea.pos = (const float*)m->w[BR_W_POS];
+    BR_TRY(launch_gemm(dt, EPI_PATCH_EMBED, fb.patches, m->pd, m->w[BR_W_PATCH_W], m->pd, B * m->n_img, H, m->pd, ea, st));
+  }
+  BR_TRY(launch_cond_broadcast(m, fb, B, st));
+  const int M = B * L;
+  for (int k = 0; k < m->NB; ++k) {
+    const int mo = k * 6 * H;
+    const char* qkv_w = (const char*)m->w[BR_W_QKV_W] + (size_t)k * 3 * H * H * es;
+    const char* proj_w = (const char*)m->w[BR_W_PROJ_W] + (size_t)k * H * H * es;
+    const char* fc1_w = (const char*)m->w[BR_W_FC1_W] + (size_t)k * m->R * H * H * es;
+    const char* fc2_w = (const char*)m->w[BR_W_FC2_W] + (size_t)k * m->R * H * H * es;
+    BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, M, L, L, H, fb.mods, m->A, mo, mo + H, fb.condmap, st));
+    {
+      EpiArgs ea{};
+      ea.bias = (const float*)m->w[BR_W_QKV_B] + (size_t)k * 3 * H;
+      ea.out = fb.qkv;
+      ea.ldo = 3 * H;
+      BR_TRY(launch_gemm(dt, EPI_BIAS, fb.xn, H, qkv_w, H, M, 3 * H, H, ea, st));
+    }
+    BR_TRY(launch_attention(dt, fb.qkv, fb.xn, B, L, m->NH, m->DH, st));  // xn is free again: attention output
+    {
+      EpiArgs ea{};
+      ea.bias = (const float*)m->w[BR_W_PROJ_B] + (size_t)k * H;
+      ea.out = fb.x;
+      ea.ldo = H;
+      ea.mods = fb.mods;
+      ea.A = m->A;
+      ea.gate_off = mo + 2 * H;
+      ea.condmap = fb.condmap;
+      ea.L = L;
+      BR_TRY(launch_gemm(dt, EPI_BIAS_GATE_RES, fb.xn, H, proj_w, H, M, H, H, ea, st));
+    }
+    BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, M, L, L, H, fb.mods, m->A, mo + 3 * H, mo + 4 * H, fb.condmap, st));
+    {
+      EpiArgs ea{};
+      ea.bias = (const float*)m->w[BR_W_FC1_B] + (size_t)k * m->R * H;
+      ea.out = fb.hid;
+      ea.ldo = m->R * H;
+      BR_TRY(launch_gemm(dt, EPI_BIAS_GELU, fb.xn, H, fc1_w, H, M, m->R * H, H, ea, st));
+    }
+    {
+      EpiArgs ea{};
+      ea.bias = (const float*)m->w[BR_W_FC2_B] + (size_t)k * H;
+      ea.out = fb.x;
+      ea.ldo = H;
+      ea.mods = fb.mods;
+      ea.A = m->A;
+      ea.gate_off = mo + 5 * H;
+      ea.condmap = fb.condmap;
+      ea.L = L;
+      BR_TRY(launch_gemm(dt, EPI_BIAS_GATE_RES, fb.hid, m->R * H, fc2_w, m->R * H, M, H, m->R * H, ea, st));
+    }
+  }
+  const int mo = m->NB * 6 * H;
+  BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, B * m->n_img, m->n_img, L, H, fb.mods, m->A, mo, mo + H, fb.condmap, st));
+  {
+    EpiArgs ea{};
+    const br_model_cfg& c = m->cfg;
+    ea.bias = (const float*)m->w[BR_W_FINAL_B];
+    ea.out = v_out;
+    ea.n_img = m->n_img;
+    ea.vrows = fb.vrows;
+    ea.D = m->D;
+    ea.lt = c.latent_t; ea.lh = c.latent_h; ea.lw = c.latent_w;
+    ea.pt = c.patch_t; ea.ph = c.patch_h; ea.pw = c.patch_w;
+    ea.gh = m->gh; ea.gw = m->gw;
+    BR_TRY(launch_gemm(dt, EPI_UNPATCH, fb.xn, H, m->w[BR_W_FINAL_W], H, B * m->n_img, m->pd, H, ea, st));
+  }
+#undef BR_TRY
+  return BR_OK;
+}
+
+}  // namespace br
+
+using namespace br;
+
+extern "C" br_status br_model_create(const br_model_cfg* cfg, const void* const* weight_ptrs, int32_t n_ptrs,
+                                     br_model** out) {
+  BR_REQUIRE(cfg && weight_ptrs && out, BR_EINVAL, "br_model_create: NULL argument");
+  BR_REQUIRE(n_ptrs == BR_W_COUNT, BR_EINVAL, "br_model_create: n_ptrs must be BR_W_COUNT");
+  const br_model_cfg& c = *cfg;
+  BR_REQUIRE(c.dtype == BR_F32 || c.dtype == BR_BF16, BR_EINVAL, "br_model_create: unknown dtype");
+  BR_REQUIRE(c.n_blocks >= 1 && c.hidden >= 1 && c.n_heads >= 1 && c.mlp_ratio >= 1 && c.latent_c >= 1 &&
+                 c.latent_t >= 1 && c.latent_h >= 1 && c.latent_w >= 1 && c.patch_t >= 1 && c.patch_h >= 1 &&
+                 c.patch_w >= 1 && c.n_cond_tokens >= 1 && c.cond_dim >= 1,
+             BR_EINVAL, "br_model_create: sizes must be positive");
+  BR_REQUIRE(c.hidden % c.n_heads == 0, BR_ESHAPE, "br_model_create: hidden must be divisible by n_heads");
+  BR_REQUIRE(c.latent_t % c.patch_t == 0 && c.latent_h % c.patch_h == 0 && c.latent_w % c.patch_w == 0, BR_ESHAPE,
+             "br_model_create: latent dims must be divisible by the patch");
+  const long long D = (long long)c.latent_c * c.latent_t * c.latent_h * c.latent_w;
+  const int pd = c.latent_c * c.patch_t * c.patch_h * c.patch_w, dh = c.hidden / c.n_heads;
+  BR_REQUIRE(D % 4 == 0, BR_ESHAPE, "br_model_create: latent size must be a multiple of 4");
+  BR_REQUIRE(c.hidden % 4 == 0 && pd % 4 == 0, BR_ESHAPE, "br_model_create: hidden and patch dim must be multiples of 4");
+  if (c.dtype == BR_BF16) {
+    BR_REQUIRE(dh == 64 || dh == 128, BR_ESHAPE, "br_model_create: bf16 head dim must be 64 or 128");
+    BR_REQUIRE(c.hidden % 64 == 0 && c.cond_dim % 64 == 0 && pd % 64 == 0, BR_ESHAPE,
+               "br_model_create: bf16 needs hidden, cond_dim and patch dim divisible by 64");
+  } else {
+    BR_REQUIRE(dh == 16 || dh == 32 || dh == 64 || dh == 128, BR_ESHAPE,
+               "br_model_create: fp32 head dim must be 16, 32, 64 or 128");
+  }
+  for (int i = 0; i < BR_W_COUNT; ++i) {
+    BR_REQUIRE(weight_ptrs[i] != nullptr, BR_EINVAL, "br_model_create: NULL weight pointer");
+    BR_REQUIRE(((uintptr_t)weight_ptrs[i] & 15) == 0, BR_EINVAL, "br_model_create: weight pointers must be 16-byte aligned");
+  }
+  br_model* m = new (std::nothrow) br_model();
+  BR_REQUIRE(m != nullptr, BR_ENOMEM, "br_model_create: out of host memory");
+  m->cfg = c;
+  for (int i = 0; i < BR_W_COUNT; ++i) m->w[i] = weight_ptrs[i];
+  m->H = c.hidden; m->NB = c.n_blocks; m->NH = c.n_heads; m->DH = dh; m->R = c.mlp_ratio;
+  m->gt = c.latent_t / c.patch_t; m->gh = c.latent_h / c.patch_h; m->gw = c.latent_w / c.patch_w;
+  m->n_img = m->gt * m->gh * m->gw;
+  m->pd = pd; m->Nc = c.n_cond_tokens; m->cd = c.cond_dim;
+  m->L = m->n_img + m->Nc;
+  m->A = c.n_blocks * 6 * c.hidden + 2 * c.hidden;
+  m->D = D;
+  *out = m;
+  return BR_OK;
+}
+
+extern "C" void br_model_free(br_model* m) { delete m; }

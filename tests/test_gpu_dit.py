@@ -1,0 +1,159 @@
+"""GPU parity of the velocity network: single ops against numpy fp64 on the same
+inputs, and the whole forward against the oracle, teacher-forced (fp32: relative
+L2 error <= 1e-4; bf16: <= 2e-2)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dit
+from paper_2509_06040_amd import binding as br
+from paper_2509_06040_amd import synth
+from gpu_util import DEV, bytes_buffer, cond_dev, dev, host, make_model, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf(a):
+    return synth.from_bf16_bits(synth.to_bf16_bits(a))
+
+
+@pytest.mark.parametrize("M,N,K", [(37, 64, 16), (130, 192, 64), (300, 100, 256)])
+def test_gemm_fp32(lib, M, N, K):
+    rng = np.random.default_rng(M)
+    A, W, b = (rng.standard_normal(s).astype(np.float32) for s in ((M, K), (N, K), (N,)))
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + b
+    out = torch.empty((M, N), device=DEV)
+    br.op_gemm(br.F32, 0, dev(A), dev(W), dev(b), out)
+    assert rel_l2(host(out), ref) < 1e-6
+    br.op_gemm(br.F32, 1, dev(A), dev(W), dev(b), out)
+    assert rel_l2(host(out), dit.gelu_tanh(ref)) < 1e-5
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, -1])
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (129, 64, 64), (1101, 384, 128), (2 * 1101 + 5, 1024, 256), (700, 36, 192)])
+def test_gemm_bf16_every_tile_shape(lib, variant, M, N, K):
+    rng = np.random.default_rng(M + N)
+    A, W = _bf(rng.standard_normal((M, K)).astype(np.float32)), _bf(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
+    b = rng.standard_normal(N).astype(np.float32)
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + b
+    Ad, Wd = dev(A, torch.bfloat16), dev(W, torch.bfloat16)
+    out32 = torch.full((M, N), -9.0, device=DEV)
+    br.op_gemm(br.BF16, 4, Ad, Wd, dev(b), out32, variant=variant)
+    assert rel_l2(host(out32), ref) < 1e-5, rel_l2(host(out32), ref)
+    out16 = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    br.op_gemm(br.BF16, 0, Ad, Wd, dev(b), out16, variant=variant)
+    assert np.array_equal(host(out16), _bf(host(out32)))          # same accumulators, rounded once
+    br.op_gemm(br.BF16, 1, Ad, Wd, dev(b), out16, variant=variant)
+    assert rel_l2(host(out16), dit.gelu_tanh(ref)) < 4e-3
+
+
+def test_gemm_gated_residual_epilogue(lib):
+    rng = np.random.default_rng(0)
+    L, B, N, K, C, Astr = 50, 3, 128, 64, 2, 700
+    M = L * B
+    A, W = _bf(rng.standard_normal((M, K)).astype(np.float32)), _bf(rng.standard_normal((N, K)).astype(np.float32) * 0.1)
+    b, x0 = rng.standard_normal(N).astype(np.float32), rng.standard_normal((M, N)).astype(np.float32)
+    mods = rng.standard_normal((C, Astr)).astype(np.float32)
+    cond = np.array([1, 0, 1], np.int32)
+    gate = mods[cond][:, 256:256 + N]
+    ref = x0 + np.repeat(gate, L, axis=0) * (A.astype(np.float64) @ W.astype(np.float64).T + b)
+    for dt, tol in ((br.BF16, 1e-5), (br.F32, 1e-6)):
+        x = dev(x0.copy())
+        tdt = torch.bfloat16 if dt == br.BF16 else torch.float32
+        br.op_gemm(dt, 2, dev(A, tdt), dev(W, tdt), dev(b), x, mods=dev(mods), gate_off=256, cond=dev(cond), L=L)
+        assert rel_l2(host(x), ref) < tol
+
+
+def _attention_ref(qkv, nh):
+    B, L, H3 = qkv.shape
+    H = H3 // 3
+    return np.stack([dit.attention(qkv[b, :, :H], qkv[b, :, H:2 * H], qkv[b, :, 2 * H:], nh) for b in range(B)])
+
+
+@pytest.mark.parametrize("dh,nh,L,B", [(16, 4, 24, 2), (32, 2, 100, 1), (64, 2, 77, 1), (128, 1, 130, 2)])
+def test_attention_fp32(lib, dh, nh, L, B):
+    rng = np.random.default_rng(dh + L)
+    qkv = rng.standard_normal((B, L, 3 * nh * dh)).astype(np.float32)
+    out = torch.empty((B, L, nh * dh), device=DEV)
+    br.op_attention(br.F32, dev(qkv), out, nh)
+    assert rel_l2(host(out), _attention_ref(qkv.astype(np.float64), nh)) < 2e-6
+
+
+@pytest.mark.parametrize("dh,nh,L,B", [(64, 2, 1, 1), (64, 3, 77, 2), (64, 2, 1101, 1), (128, 2, 130, 2), (128, 1, 640, 1),
+                                        (64, 1, 128, 1)])
+def test_attention_bf16(lib, dh, nh, L, B):
+    rng = np.random.default_rng(dh + L)
+    qkv = _bf(rng.standard_normal((B, L, 3 * nh * dh)).astype(np.float32) * 1.5)
+    out = torch.full((B, L, nh * dh), 3.0, dtype=torch.bfloat16, device=DEV)
+    br.op_attention(br.BF16, dev(qkv, torch.bfloat16), out, nh)
+    ref = _attention_ref(qkv.astype(np.float64), nh)
+    err = rel_l2(host(out), ref)
+    assert err < 6e-3, err                       # bf16 probabilities and output rounding
+
+
+@pytest.mark.parametrize("dt", [br.F32, br.BF16])
+def test_ln_modulate(lib, dt):
+    rng = np.random.default_rng(1)
+    B, L, n_img, H, C, Astr = 3, 9, 7, 192, 2, 1000
+    x = (rng.standard_normal((B * L, H)) * 3 + 1).astype(np.float32)
+    mods = rng.standard_normal((C, Astr)).astype(np.float32) * 0.3
+    cond = np.array([0, 1, 1], np.int32)
+    tdt = torch.bfloat16 if dt == br.BF16 else torch.float32
+    tol = 4e-3 if dt == br.BF16 else 2e-6
+    for rows, so, co in ((L, 0, H), (n_img, 400, 600)):
+        out = torch.empty((B * rows, H), dtype=tdt, device=DEV)
+        br.op_ln_modulate(dt, dev(x), out, rows, L, dev(mods), so, co, dev(cond))
+        xs = x.reshape(B, L, H)[:, :rows].astype(np.float64)
+        m = mods[cond].astype(np.float64)
+        ref = dit.layer_norm(xs) * (1 + m[:, None, co:co + H]) + m[:, None, so:so + H]
+        assert rel_l2(host(out).reshape(B, rows, H), ref) < tol
+
+
+def _velocity_case(cfg, n_cond, B, t, seed, std=0.02):
+    W = synth.make_weights(cfg, seed, std)
+    D = synth.model_sizes(cfg)["D"]
+    z = synth.random_latents(B, D, seed + 1)
+    cond = synth.cond_tokens(cfg, n_cond, seed + 2)
+    cidx = np.arange(B) % n_cond
+    model = make_model(cfg, W)
+    ws = bytes_buffer(br.workspace_bytes(None, model, B))
+    v = torch.full((B, D), 5.0, device=DEV)
+    br.velocity(model, dev(z), t, cond_dev(cfg, cond), cidx, v, ws)
+    rnd = dit.round_bf16 if cfg["dtype"] == synth.BF16 else dit.identity
+    ref = dit.forward(cfg, W, z, t, cond, cidx, act_round=rnd)
+    return host(v), ref, (model, W, z, cond, cidx)
+
+
+def test_velocity_tiny_fp32_matches_oracle(lib):
+    cfg = synth.WORKLOADS["tiny"]["model"]
+    for t, std in ((1.0, 0.02), (0.37, 0.02), (0.05, 0.2)):
+        got, ref, _ = _velocity_case(cfg, 2, 5, t, 0, std)
+        for b in range(5):
+            assert rel_l2(got[b], ref[b]) <= 1e-4, (t, b, rel_l2(got[b], ref[b]))   # stated fp32 tolerance
+
+
+def test_velocity_fp32_other_shapes(lib):
+    # temporal patches, head dim 32, ragged token count
+    cfg = synth.model_cfg(2, 64, 2, (3, 4, 6, 10), (2, 2, 2), 5, synth.F32)
+    got, ref, _ = _velocity_case(cfg, 3, 4, 0.6, 3, 0.1)
+    assert max(rel_l2(got[b], ref[b]) for b in range(4)) <= 1e-4
+
+
+def test_velocity_small_bf16_matches_oracle(lib):
+    for cfg in (synth.model_cfg(2, 128, 2, (16, 1, 16, 20), (1, 2, 2), 13, synth.BF16),          # d_h 64, L = 93
+                synth.model_cfg(1, 256, 2, (16, 2, 8, 12), (1, 2, 2), 70, synth.BF16)):         # d_h 128, L = 166
+        got, ref, _ = _velocity_case(cfg, 2, 3, 0.5, 1, 0.05)
+        for b in range(3):
+            assert rel_l2(got[b], ref[b]) <= 2e-2, rel_l2(got[b], ref[b])                       # stated bf16 tolerance
+
+
+def test_velocity_chunked_batches_agree(lib):
+    cfg = synth.WORKLOADS["tiny"]["model"]
+    got, ref, (model, W, z, cond, cidx) = _velocity_case(cfg, 2, 5, 0.5, 4)
+    small = bytes_buffer(br.workspace_bytes(None, model, 2) + 64)       # forces chunks of <= 2
+    v2 = torch.empty_like(torch.from_numpy(got)).to(DEV)
+    br.velocity(model, dev(z), 0.5, cond_dev(cfg, cond), cidx, v2, small)
+    assert np.array_equal(host(v2), got)
+    with pytest.raises(br.BranchRolloutError) as e:
+        br.velocity(model, dev(z), 0.5, cond_dev(cfg, cond), cidx, v2, bytes_buffer(256))
+    assert e.value.code == -4

@@ -1,0 +1,86 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol,
+and its host logic (topology, depth masks, argument validation) agrees with the
+oracle bit for bit.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import prune, tree
+from paper_2509_06040_amd import binding as br
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = br.load()
+    declared = set()
+    for header in ("branchrollout.h", "branchrollout_ops.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        declared |= set(re.findall(r"\b(br_[a-z0-9_]+)\s*\(", text))
+    assert len(declared) >= 24
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(br.EXPORTS)
+
+
+@pytest.mark.parametrize("T,splits,K", [(8, (2, 4, 6), 2), (20, (4, 8, 12, 16), 2), (20, (0, 3, 6, 9), 3),
+                                        (16, (3, 6, 9, 12), 4), (5, (), 2), (6, (1, 2), 1), (3, (0, 1, 2), 2)])
+def test_tree_build_is_bit_exact_with_the_oracle(T, splits, K):
+    t = br.Tree(T, splits, K, n_tree=3)
+    o = tree.tree_build(T, splits, K)
+    assert (t.n_nodes, t.n_edges, t.n_leaves, t.n_tree) == (o["n_nodes"], o["n_edges"], o["n_leaves"], 3)
+    for name in ("width", "off", "parent", "depth", "branch", "leaf_lo", "leaf_hi"):
+        got = getattr(t, name)
+        assert got.dtype == np.int32 and np.array_equal(got, o[name]), name
+
+
+def test_paper_tree_sizes_through_the_library():
+    # Table 1 / Table 3 NFE figures: 219, 185, 151 nodes over 16 leaves
+    for splits, nodes in (((0, 3, 6, 9), 219), ((0, 4, 8, 12), 185), ((0, 5, 10, 15), 151)):
+        t = br.Tree(20, splits, 2)
+        assert (t.n_nodes, t.n_leaves) == (nodes, 16)
+
+
+def test_tree_build_rejects_bad_arguments():
+    for args in ((0, (), 2), (4, (4,), 2), (4, (2, 1), 2), (4, (1, 1), 2), (4, (-1,), 2), (4, (1,), 0), (2000, (), 2)):
+        with pytest.raises(br.BranchRolloutError) as e:
+            br.Tree(*args)
+        assert e.value.code == -1 and "br_tree_build" in str(e.value)
+    with pytest.raises(br.BranchRolloutError):
+        br.Tree(4, (1,), 2, n_tree=0)
+    with pytest.raises(br.BranchRolloutError):          # 2^31 nodes
+        br.Tree(40, tuple(range(32)), 2)
+
+
+def test_depth_masks_match_the_oracle():
+    for it in (0, 29, 30, 95, 300, 3000):
+        for stop in (20, 18):
+            assert np.array_equal(br.depth_mask_window(20, 9, 4, it, 30, stop), prune.depth_mask_window(20, 9, 4, it, 30, stop))
+    # the seeded subset ranks raw Philox words: host generator and oracle agree bit for bit
+    for seed in (0, 42, 1223627, (1 << 40) + 17):
+        for n_drop in (0, 4, 7):
+            assert np.array_equal(br.depth_mask_seeded(20, n_drop, seed), prune.depth_mask_seeded(20, n_drop, seed))
+    with pytest.raises(br.BranchRolloutError):
+        br.depth_mask_seeded(5, 6, 1)
+
+
+def test_model_create_validates_shapes():
+    lib = br.load()
+    cfg = br.ModelCfg(2, 64, 4, 4, 4, 1, 8, 8, 1, 2, 2, 8, 64, br.F32)
+    fake = (C.c_void_p * br.W_COUNT)(*[0x1000] * br.W_COUNT)      # never dereferenced by create
+    h = C.c_void_p()
+    assert lib.br_model_create(C.byref(cfg), fake, br.W_COUNT, C.byref(h)) == 0
+    lib.br_model_free(h)
+    bad = br.ModelCfg(2, 64, 4, 4, 4, 1, 8, 8, 1, 2, 2, 8, 64, br.BF16)   # head dim 16 in bf16
+    assert lib.br_model_create(C.byref(bad), fake, br.W_COUNT, C.byref(h)) == -3
+    assert b"head dim" in lib.br_last_error()
+    bad = br.ModelCfg(2, 64, 4, 4, 4, 1, 9, 8, 1, 2, 2, 8, 64, br.F32)    # 9 not divisible by patch 2
+    assert lib.br_model_create(C.byref(bad), fake, br.W_COUNT, C.byref(h)) == -3
+    assert lib.br_model_create(C.byref(cfg), fake, br.W_COUNT - 1, C.byref(h)) == -1
+    fake[3] = 0x1004                                                       # misaligned
+    assert lib.br_model_create(C.byref(cfg), fake, br.W_COUNT, C.byref(h)) == -1
+    assert lib.br_workspace_bytes(None, None, 4) == 0
