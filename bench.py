@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the BranchGRPO tree-rollout hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic prompts:
+  br_rollout (tree rollout under the behaviour policy) -> br_leaf_reward ->
+  br_fuse_advantage -> br_prune -> br_logprob (re-evaluation of the kept edges
+  under perturbed weights) -> br_grpo_objective.
+Workload: the image-shaped tree (DiT 12 blocks, hidden 1024, 16 heads, latent
+16x64x64, 1024+77 tokens, T = 20, splits {4,8,12,16}, K = 2, 4 prompts -> 64
+leaves), with Extreme-4 width pruning and 4 seeded dropped depths.
+
+Prints ONE JSON line: leaf trajectories/s of the whole step, with the roofline
+of the dominant kernel (measured with HIP events around every launch inside the
+timed region) and the CPU oracle timed on a bounded sample beside it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, data-sheet figure
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+GEMM_NAMES = {0: "bias", 1: "bias_gelu", 2: "bias_gate_residual", 3: "patch_embed", 4: "bias_f32", 5: "unpatchify"}
+TILE_NAMES = {0: "128x128", 1: "256x128", 2: "256x256", 3: "128x256"}
+
+
+def kernel_label(kid):
+    if kid < 100:
+        return "gemm_bf16[%s,%s]" % (GEMM_NAMES[kid // 8], TILE_NAMES[kid % 8])
+    if kid < 200:
+        return "attn_bf16[d%d]" % (kid - 100)
+    return {200: "sde_step", 201: "logp_eval", 300: "ln_modulate"}[kid]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="image", choices=["image", "tiny"])
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not time single launches in the timed region")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-flat", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (conditions are independent trees and would shard "
+                 "across GPUs without collectives); run with --gpus 1")
+
+    import torch
+    from paper_2509_06040_amd import binding as br
+    from paper_2509_06040_amd import synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    br.load()
+    dev = "cuda"
+    wl = synth.WORKLOADS[args.workload]
+    cfg, T, C = wl["model"], wl["T"], wl["n_cond"]
+    sz = synth.model_sizes(cfg)
+    D, L, H, NB = sz["D"], sz["L"], cfg["hidden"], cfg["n_blocks"]
+    latent = (cfg["latent_c"], cfg["latent_t"], cfg["latent_h"], cfg["latent_w"])
+    tdt = torch.bfloat16 if cfg["dtype"] == synth.BF16 else torch.float32
+
+    W = synth.make_weights(cfg, 0)
+    W2 = synth.perturb_weights(cfg, W, 11, 0.002)
+    model = br.Model(cfg, br.upload_weights(cfg, W))
+    model2 = br.Model(cfg, br.upload_weights(cfg, W2))
+    cond_np = synth.cond_tokens(cfg, C)
+    cond = torch.from_numpy(cond_np).to(dev).to(tdt)
+    sched = synth.schedule(T, wl["kappa"], logp_mean=True)
+    tree = br.Tree(T, wl["splits"], wl["K"], n_tree=C)
+    n_leaves = C * tree.n_leaves
+    n = C * tree.n_nodes
+    groups = list(range(C))
+    w_rew = torch.from_numpy(synth.reward_vector(D, 7)).to(dev)
+    kind = {"linear": br.REWARD_LINEAR, "tanh": br.REWARD_TANH}[wl["reward"]]
+    depth_mask = br.depth_mask_seeded(T, min(4, T), synth.DATA_SEED)
+    b_extreme = max(1, tree.n_leaves // 4)
+
+    z = torch.empty((n, D), device=dev)
+    logp = torch.empty(n, device=dev)
+    rew = torch.empty(n_leaves, device=dev)
+    rbar, adv = torch.empty(n, device=dev), torch.empty(n, device=dev)
+    kept = torch.empty(C * tree.n_edges, dtype=torch.int32, device=dev)
+    n_kept = torch.zeros(1, dtype=torch.int32, device=dev)
+    logp_new = torch.empty(C * tree.n_edges, device=dev)
+    J = torch.empty(1, device=dev)
+    ws = torch.empty(br.workspace_bytes(tree, model, n_leaves), dtype=torch.uint8, device=dev)
+    rs = torch.empty(max(256, br.reward_scratch_bytes(tree, kind, latent)), dtype=torch.uint8, device=dev)
+
+    phase_ms = {}
+
+    def step(seed, timed):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+        if timed:
+            ev[0].record()
+        br.rollout(tree, model, sched, seed, groups, cond, z, logp, None, ws)
+        if timed:
+            ev[1].record()
+        br.leaf_reward(tree, z, kind, w_rew, 0.0, latent, rew, rs)
+        br.fuse_advantage(tree, rew, logp, 1.0, 1e-8, 0, synth.ADV_CLIP, rbar, adv)
+        br.prune(tree, rew, br.PRUNE_EXTREME, b_extreme, depth_mask, kept, n_kept)
+        nk = int(n_kept.cpu()[0])                       # the only host round trip of a step
+        ids = kept[:nk].cpu().numpy()
+        if timed:
+            ev[2].record()
+        br.logprob(tree, model2, sched, cond, z, ids, logp_new, ws)
+        br.grpo_objective(logp_new, logp, adv, kept, nk, synth.CLIP_RANGE, J)
+        if timed:
+            ev[3].record()
+        return ev, nk
+
+    for i in range(args.warmup):
+        step(synth.SAMPLER_SEED + i, False)
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        br.profile_enable(True)
+        br.profile_read()
+    t0 = time.perf_counter()
+    evs = [step(synth.SAMPLER_SEED + 100 + i, True) for i in range(args.steps)]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = {}
+    if not args.no_kernel_events:
+        prof = br.profile_read()
+        br.profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    nk = evs[-1][1]
+    for name, a, b in (("rollout", 0, 1), ("reward_fuse_prune", 1, 2), ("logprob_objective", 2, 3)):
+        phase_ms[name] = float(np.mean([e[0][a].elapsed_time(e[0][b]) for e in evs]))
+    value = n_leaves / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (largest total time among the instrumented ones)
+    kernels = {}
+    for kid, (work, ms, cnt) in prof.items():
+        mfma = kid < 200
+        ach = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
+        peak = PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS
+        kernels[kernel_label(kid)] = dict(bound="mfma" if mfma else "hbm", launches=int(cnt), total_ms=round(ms, 3),
+                                          avg_us=round(ms * 1e3 / cnt, 2), achieved=round(ach, 2),
+                                          unit="TFLOP/s" if mfma else "GB/s", frac=round(ach / peak, 4))
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
+        k = kernels[dom]
+        roofline = dict(kernel=dom, bound=k["bound"], achieved=k["achieved"], peak=PEAK_BF16_TFLOPS if k["bound"] == "mfma" else PEAK_HBM_GBS,
+                        unit=k["unit"], frac=k["frac"], traffic=None, avg_launch_us=k["avg_us"], launches=k["launches"])
+        mf = [v for v in kernels.values() if v["bound"] == "mfma"]
+        tot_flop = sum(v["achieved"] * v["total_ms"] for v in mf)
+        tot_ms = sum(v["total_ms"] for v in mf)
+        roofline["network_mfma_frac"] = round(tot_flop / tot_ms / PEAK_BF16_TFLOPS, 4) if tot_ms else None
+
+    # ---- model FLOPs of a step (2MNK per GEMM, 4 L^2 H per attention block) / wall time
+    fwd_flop = NB * (24.0 * L * H * H + 4.0 * L * L * H) + 4.0 * sz["n_img"] * sz["patch_dim"] * H
+    n_eval_roll = C * int(sum(tree.width[:T]))
+    depth_of = tree.depth
+    par = set()
+    for g in (kept[:nk].cpu().numpy() if nk else []):
+        cc, nn_ = divmod(int(g), tree.n_nodes)
+        par.add(cc * tree.n_nodes + int(tree.parent[nn_]))
+    n_eval_lp = len(par)
+    step_mfma_util = (n_eval_roll + n_eval_lp) * fwd_flop / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
+    rollout_mfma_util = n_eval_roll * fwd_flop / (phase_ms["rollout"] * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
+
+    # ---- flat N*T sequential rollout on the same GPU, same kernels (K = 1 trees)
+    flat = None
+    if not args.no_flat:
+        ftree = br.Tree(T, (), 1, n_tree=n_leaves)
+        fz = torch.empty((n_leaves * ftree.n_nodes, D), device=dev)
+        flp = torch.empty(n_leaves * ftree.n_nodes, device=dev)
+        fcond = cond.repeat_interleave(tree.n_leaves, dim=0).contiguous()
+        fgroups = [c for c in range(C) for _ in range(tree.n_leaves)]     # "init same noise" per prompt
+        fws = torch.empty(br.workspace_bytes(ftree, model, n_leaves), dtype=torch.uint8, device=dev)
+        br.rollout(ftree, model, sched, 1, fgroups, fcond, fz, flp, None, fws)
+        torch.cuda.synchronize()
+        f0 = time.perf_counter()
+        reps = 2
+        for i in range(reps):
+            br.rollout(ftree, model, sched, 2 + i, fgroups, fcond, fz, flp, None, fws)
+        torch.cuda.synchronize()
+        fms = (time.perf_counter() - f0) * 1e3 / reps
+        flat = dict(ms=round(fms, 2), leaf_traj_per_s=round(n_leaves / (fms * 1e-3), 2),
+                    tree_rollout_ms=round(phase_ms["rollout"], 2),
+                    tree_rollout_leaf_traj_per_s=round(n_leaves / (phase_ms["rollout"] * 1e-3), 2),
+                    speedup_tree_vs_flat=round(fms / phase_ms["rollout"], 3), network_evals_flat=n_leaves * T,
+                    network_evals_tree=n_eval_roll)
+        del fz, flp, fws
+
+    # ---- the CPU oracle on a bounded sample, extrapolated to a step
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dit as odit
+        from oracle import philox as ophilox
+        from oracle import sde as osde
+        threads = os.cpu_count()
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [threads])
+        except Exception:
+            pass
+        rnd = odit.round_bf16 if cfg["dtype"] == synth.BF16 else odit.identity
+        zs = synth.random_latents(1, D, 3)
+        c0 = time.perf_counter()
+        v = odit.forward(cfg, W, zs, float(sched["t"][3]), cond_np, [0], act_round=rnd)
+        c1 = time.perf_counter()
+        mu = osde.drift_mean(zs[0].astype(np.float64), v[0], sched["t"][3], sched["t"][4], sched["sigma"][3])
+        _, std = osde.step_coefficients(sched["t"][3], sched["t"][4], sched["sigma"][3])
+        xi = ophilox.normals(1, 5, 3, ophilox.TAG_ETA, D)
+        osde.transition_logp(mu + std * xi, mu, std, True)
+        c2 = time.perf_counter()
+        per_eval, per_sde = c1 - c0, c2 - c1
+        est = (n_eval_roll + n_eval_lp) * per_eval + (n - C + nk) * per_sde
+        cpu = dict(value=round(n_leaves / est, 5), unit="leaf trajectories/s", cores=int(threads), kind="oracle",
+                   sample="1 oracle network evaluation (%.2f s) + 1 oracle SDE step/log-prob (%.3f s) at full size, "
+                          "extrapolated to the %d evaluations and %d transitions of one step"
+                          % (per_eval, per_sde, n_eval_roll + n_eval_lp, n - C + nk))
+
+    out = dict(metric="leaf trajectories/sec (tree vs flat N*T rollout); DiT-fwd MFMA util %", value=round(value, 3),
+               unit="leaf trajectories/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16" if cfg["dtype"] == synth.BF16 else "f32", data="synthetic",
+               config=dict(workload="%s tree: DiT %d blocks hidden %d, L=%d, D=%d, T=%d splits %s K=%d, %d prompts x %d "
+                                    "leaves; Extreme-%d width pruning + %d seeded dropped depths, log-prob "
+                                    "re-evaluation of %d kept edges under perturbed weights"
+                                    % (args.workload, NB, H, L, D, T, list(wl["splits"]), wl["K"], C, tree.n_leaves,
+                                       b_extreme, int(depth_mask.sum()), nk),
+                           prompts=C, leaves_per_prompt=int(tree.n_leaves), n_nodes=int(tree.n_nodes)),
+               phase_ms={k: round(v, 3) for k, v in phase_ms.items()},
+               mfma_util_step=round(step_mfma_util, 4), mfma_util_rollout=round(rollout_mfma_util, 4),
+               network_evals=dict(rollout=n_eval_roll, logprob=n_eval_lp, flop_per_eval=fwd_flop),
+               roofline=roofline, kernels=kernels, flat_rollout=flat, cpu_baseline=cpu)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -39,6 +39,17 @@ br_status br_op_ln_modulate(int32_t dtype, const float* x, void* out, int32_t n_
                             int32_t mods_stride, int32_t shift_off, int32_t scale_off,
                             const int32_t* cond, void* stream);
 
+/* Per-launch timing of the main kernels with HIP events recorded on the launch
+ * stream around each launch (off by default; single-threaded use).  While enabled
+ * every instrumented launch adds one record; br_profile_read waits for the
+ * recorded events, sums work (flops for GEMM and attention, bytes for the others)
+ * and milliseconds per kernel id, clears the records and returns up to max_ids
+ * entries.  Ids: GEMM = epilogue*8 + tile variant; attention = 100 + head dim;
+ * 200 SDE step, 201 log-prob re-evaluation, 300 LayerNorm-modulate. */
+br_status br_profile_enable(int32_t on);
+br_status br_profile_read(int32_t max_ids, int32_t* ids, double* work, double* ms,
+                          int64_t* launches, int32_t* n_ids);
+
 #ifdef __cplusplus
 }
 #endif

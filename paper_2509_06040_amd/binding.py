@@ -29,7 +29,7 @@ EXPORTS = (
     "br_workspace_bytes", "br_rollout", "br_logprob", "br_fuse_advantage", "br_prune", "br_reward_scratch_bytes",
     "br_leaf_reward", "br_grpo_objective", "br_velocity", "br_sde_scratch_bytes", "br_sde_step", "br_root_noise",
     "br_noise_stream", "br_depth_mask_window", "br_depth_mask_seeded", "br_op_gemm", "br_op_attention",
-    "br_op_ln_modulate",
+    "br_op_ln_modulate", "br_profile_enable", "br_profile_read",
 )
 
 
@@ -274,3 +274,17 @@ def op_ln_modulate(dtype, x, out, rows_per_sample, L_in, mods, shift_off, scale_
     _check(load().br_op_ln_modulate(C.c_int32(dtype), _p(x), _p(out), C.c_int32(n_rows), C.c_int32(rows_per_sample),
                                     C.c_int32(L_in), C.c_int32(H), _p(mods), C.c_int32(mods.shape[1]),
                                     C.c_int32(shift_off), C.c_int32(scale_off), _p(cond), _stream()))
+
+
+def profile_enable(on):
+    _check(load().br_profile_enable(C.c_int32(1 if on else 0)))
+
+
+def profile_read(max_ids=64):
+    """-> {kernel id: (work, milliseconds, launches)} since the last read."""
+    ids = (C.c_int32 * max_ids)()
+    work, ms = (C.c_double * max_ids)(), (C.c_double * max_ids)()
+    launches = (C.c_int64 * max_ids)()
+    n = C.c_int32()
+    _check(load().br_profile_read(C.c_int32(max_ids), ids, work, ms, launches, C.byref(n)))
+    return {ids[i]: (work[i], ms[i], launches[i]) for i in range(n.value)}

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbranchrollout.so")
 SOURCES = ["tree.cpp", "sde_kernels.hip", "tree_kernels.hip", "dit_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip",
-           "forward.hip", "api.hip", "ops_api.hip"]
+           "forward.hip", "api.hip", "ops_api.hip", "prof.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -10,6 +10,7 @@
 // layout; V is staged transposed ([d][key]) so the row operand is two 8-byte reads.
 #include "common.h"
 #include "dit.h"
+#include "prof.h"
 
 namespace br {
 
@@ -160,6 +161,7 @@ br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH
   dim3 g(cdiv(L, 128), NH, B), blk(256);
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)DH));
   const int H = NH * DH;
+  ProfScope ps(st, PROF_ATTN + DH, 4.0 * B * (double)L * L * H);
   if (DH == 64) hipLaunchKernelGGL((attn_bf16_kernel<64>), g, blk, 0, st, qkv, out, L, H, scale_log2);
   else if (DH == 128) hipLaunchKernelGGL((attn_bf16_kernel<128>), g, blk, 0, st, qkv, out, L, H, scale_log2);
   else return fail(BR_ESHAPE, "bf16 attention: head dim must be 64 or 128");

@@ -4,6 +4,7 @@
 // gemm_bf16.hip and attn_bf16.hip.
 #include "common.h"
 #include "dit.h"
+#include "prof.h"
 
 namespace br {
 
@@ -212,6 +213,7 @@ br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, i
                              hipStream_t st) {
   if (n_rows == 0) return BR_OK;
   dim3 g(cdiv(n_rows, 4)), b(256);
+  ProfScope ps(st, PROF_LN_MOD, (double)n_rows * H * (4.0 + (dtype == BR_BF16 ? 2.0 : 4.0)));
   if (dtype == BR_BF16)
     hipLaunchKernelGGL((ln_modulate_kernel<bf16>), g, b, 0, st, x, (bf16*)out, n_rows, rows_per_sample, L_in, H, mods, A,
                        shift_off, scale_off, condmap);

@@ -12,6 +12,7 @@
 // multiplied; two LDS buffers, one barrier per k-step.
 #include "common.h"
 #include "dit.h"
+#include "prof.h"
 
 namespace br {
 
@@ -179,6 +180,7 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
     const long long t2561 = (long long)cdiv(M, 256) * cdiv(N, 128);
     variant = t256 >= 512 ? 2 : (t2561 >= 512 ? 1 : 0);
   }
+  ProfScope ps(st, PROF_GEMM + MODE * 8 + variant, 2.0 * M * N * K);
   switch (variant) {
     case 0: return gemm_launch<128, 128, 2, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, st);
     case 1: return gemm_launch<256, 128, 4, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, st);

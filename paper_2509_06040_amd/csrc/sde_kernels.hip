@@ -6,6 +6,7 @@
 #include "common.h"
 #include "kernels.h"
 #include "philox.h"
+#include "prof.h"
 
 namespace br {
 
@@ -240,6 +241,8 @@ br_status launch_sde_step(const br_tree* t, const br_sched* s, uint64_t seed, in
   const int off_p = t->off[i], off_c = t->off[i + 1];
   BR_REQUIRE(n_par <= 65535, BR_ESHAPE, "sde step: more than 65535 parents in one depth are not supported");
   dim3 grid(nblk, n_par);
+  // algorithmic bytes: z and v of every parent read once, every child written once
+  ProfScope ps(st, PROF_SDE_STEP, (double)n_par * (2.0 + K) * 4.0 * (double)D);
 #define BR_SDE_ARGS z, v, v_compact, (long long)D, t->n_nodes, off_p, off_c, t->width[i], split, cf, key, i, partials
   if (K == 1) hipLaunchKernelGGL(sde_step_kernel<1>, grid, dim3(256), 0, st, BR_SDE_ARGS);
   else if (K == 2) hipLaunchKernelGGL(sde_step_kernel<2>, grid, dim3(256), 0, st, BR_SDE_ARGS);
@@ -252,6 +255,7 @@ br_status launch_sde_step(const br_tree* t, const br_sched* s, uint64_t seed, in
   }
 #undef BR_SDE_ARGS
   BR_LAUNCH_CHECK();
+  if (ps.on) { prof_end(st); ps.on = false; }
   const int n_child = n_par * K;
   hipLaunchKernelGGL(logp_finalize_kernel, dim3(n_child), dim3(64), 0, st, partials, nblk, n_child, 0.5, cf.c0,
                      cf.inv_div, cf.noise, logp, (const int*)nullptr, t->n_nodes, off_c, t->width[i + 1]);
@@ -266,9 +270,11 @@ br_status launch_logp_eval(const br_sched* s, int i, long long D, const float* z
   const StepCoef cf = step_coef(s, i, D);
   const int nblk = sde_nblk(D);
   BR_REQUIRE(n_edges <= 65535, BR_ESHAPE, "logprob: more than 65535 kept edges in one depth are not supported");
+  ProfScope ps(st, PROF_LOGP_EVAL, (double)n_edges * 3.0 * 4.0 * (double)D);
   hipLaunchKernelGGL(logp_eval_kernel, dim3(nblk, n_edges), dim3(256), 0, st, z, v, (long long)D, crow, prow, vrow, cf,
                      partials);
   BR_LAUNCH_CHECK();
+  if (ps.on) { prof_end(st); ps.on = false; }
   hipLaunchKernelGGL(logp_finalize_kernel, dim3(n_edges), dim3(64), 0, st, partials, nblk, n_edges, cf.inv_2var, cf.c0,
                      cf.inv_div, cf.noise, logp_out, out_slot, 0, 0, 1);
   BR_LAUNCH_CHECK();

@@ -74,9 +74,12 @@ def weight_shapes(cfg):
 
 
 def to_bf16_bits(a):
-    """float32 array -> uint16 bfloat16 bit patterns (round to nearest even)."""
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    r = (u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)
+    """float32 array -> uint16 bfloat16 bit patterns (round to nearest even; finite inputs)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = (u >> np.uint32(16)) & np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= np.uint32(16)
     return r.astype(np.uint16)
 
 
