@@ -10,6 +10,8 @@
 // c ^ (r & 7), which keeps both the staging writes and the operand reads free of
 // bank conflicts.  Global loads of tile k+1 are in flight while tile k is
 // multiplied; two LDS buffers, one barrier per k-step.
+#include <type_traits>
+
 #include "common.h"
 #include "dit.h"
 #include "prof.h"
@@ -18,11 +20,13 @@ namespace br {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// native vector type: arrays of HIP's uint4 struct are not promoted to registers
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int WGM, int WGN, int MODE, typename TOUT>
+template <int BM, int BN, int WGM, int WGN, int SWZ, int MODE, typename TOUT>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __restrict__ A, int lda,
                                                                   const bf16* __restrict__ W, int ldw, int M, int N,
-                                                                  int K, int tiles_m, int tiles_n,
+                                                                  int K, int tiles_m, int tiles_n, int group_n,
                                                                   Epilogue<MODE, TOUT> epi) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -30,8 +34,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __
   constexpr int CA = BM * 8 / NT, CW = BN * 8 / NT;  // 16-byte chunks per thread and tile
   static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile / thread mismatch");
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  uint4* sA = reinterpret_cast<uint4*>(smem);                 // [2][BM * 8] chunks
-  uint4* sW = sA + 2 * BM * 8;                                // [2][BN * 8] chunks
+  u32x4* sA = reinterpret_cast<u32x4*>(smem);                 // [2][BM * 8] chunks
+  u32x4* sW = sA + 2 * BM * 8;                                // [2][BN * 8] chunks
 
   // Workgroup -> tile: consecutive workgroup ids go round-robin to the 8 XCDs, so
   // give each XCD a contiguous range of tiles (n fastest): tiles that share an
@@ -43,7 +47,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __
     // XCD x owns per (+1 if x < rem) tiles starting at x*per + min(x, rem)
     wg = x * per + (x < rem ? x : rem) + i;
   }
-  const int tile_m = wg / tiles_n, tile_n = wg % tiles_n;
+  // inside an XCD's range tiles are walked in column groups of group_n tiles, rows
+  // outermost inside a group: the weight panels of a group stay in L2 while the
+  // activation panels stream through
+  int tile_m, tile_n;
+  {
+    const int gsz = tiles_m * group_n;
+    const int g = wg / gsz, idx = wg - g * gsz;
+    const int gn = min(group_n, tiles_n - g * group_n);
+    tile_m = idx / gn;
+    tile_n = g * group_n + idx - tile_m * gn;
+  }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -60,14 +74,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __
     const int id = tid + i * NT, row = id >> 3, c = id & 7;
     const int gm = min(m0 + row, M - 1);
     ga[i] = A + (size_t)gm * lda + c * 8;
-    sa_off[i] = row * 8 + (c ^ (row & 7));
+    sa_off[i] = row * 8 + (c ^ ((row >> SWZ) & 7));
   }
 #pragma unroll
   for (int i = 0; i < CW; ++i) {
     const int id = tid + i * NT, row = id >> 3, c = id & 7;
     const int gn = min(n0 + row, N - 1);
     gw[i] = W + (size_t)gn * ldw + c * 8;
-    sw_off[i] = row * 8 + (c ^ (row & 7));
+    sw_off[i] = row * 8 + (c ^ ((row >> SWZ) & 7));
   }
 
   f32x16 acc[TN][TM];
@@ -78,12 +92,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[CA], rw[CW];
+  u32x4 ra[CA], rw[CW];
   const int nk = K / 64;
 #pragma unroll
-  for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const uint4*>(ga[i]);
+  for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i]);
 #pragma unroll
-  for (int i = 0; i < CW; ++i) rw[i] = *reinterpret_cast<const uint4*>(gw[i]);
+  for (int i = 0; i < CW; ++i) rw[i] = *reinterpret_cast<const u32x4*>(gw[i]);
 #pragma unroll
   for (int i = 0; i < CA; ++i) sA[sa_off[i]] = ra[i];
 #pragma unroll
@@ -94,35 +108,40 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __
     const int cur = kt & 1;
     if (kt + 1 < nk) {
 #pragma unroll
-      for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const uint4*>(ga[i] + (size_t)(kt + 1) * 64);
+      for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + (size_t)(kt + 1) * 64);
 #pragma unroll
-      for (int i = 0; i < CW; ++i) rw[i] = *reinterpret_cast<const uint4*>(gw[i] + (size_t)(kt + 1) * 64);
+      for (int i = 0; i < CW; ++i) rw[i] = *reinterpret_cast<const u32x4*>(gw[i] + (size_t)(kt + 1) * 64);
     }
-    const uint4* cA = sA + cur * BM * 8;
-    const uint4* cW = sW + cur * BN * 8;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[TM], fw[TN];
+    const u32x4* cA = sA + cur * BM * 8;
+    const u32x4* cW = sW + cur * BN * 8;
+    // operand fragments of k-step ks+1 are read while the MFMAs of step ks run
+    bf16x8 fa[2][TM], fw[2][TN];
+    auto read_frags = [&](int ks, bf16x8* a, bf16x8* w) {
       const int c = ks * 2 + lh;
 #pragma unroll
       for (int j = 0; j < TM; ++j) {
         const int row = wm0 + j * 32 + l32;
-        fa[j] = *reinterpret_cast<const bf16x8*>(&cA[row * 8 + (c ^ (row & 7))]);
+        a[j] = *reinterpret_cast<const bf16x8*>(&cA[row * 8 + (c ^ ((row >> SWZ) & 7))]);
       }
 #pragma unroll
       for (int i = 0; i < TN; ++i) {
         const int row = wn0 + i * 32 + l32;
-        fw[i] = *reinterpret_cast<const bf16x8*>(&cW[row * 8 + (c ^ (row & 7))]);
+        w[i] = *reinterpret_cast<const bf16x8*>(&cW[row * 8 + (c ^ ((row >> SWZ) & 7))]);
       }
+    };
+    read_frags(0, fa[0], fw[0]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks + 1 < 4) read_frags(ks + 1, fa[(ks + 1) & 1], fw[(ks + 1) & 1]);
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][i], fa[ks & 1][j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
-      uint4* nA = sA + (cur ^ 1) * BM * 8;
-      uint4* nW = sW + (cur ^ 1) * BN * 8;
+      u32x4* nA = sA + (cur ^ 1) * BM * 8;
+      u32x4* nW = sW + (cur ^ 1) * BN * 8;
 #pragma unroll
       for (int i = 0; i < CA; ++i) nA[sa_off[i]] = ra[i];
 #pragma unroll
@@ -150,13 +169,219 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Deep-pipelined variant: operand tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging), BK = 32 per stage, four stages,
+// three of them in flight while the fourth is multiplied.  One tile's worth of
+// registers is freed and, more importantly, about three times as many bytes are in
+// flight per compute unit, which is what hides the L2/HBM latency.
+//
+// An LDS-direct load writes 64 lanes x 16 bytes to consecutive LDS addresses, i.e.
+// 16 tile rows of 64 bytes; the swizzle is therefore applied on the global side:
+// the lane that fills slot s of row r fetches k-chunk s ^ ((r >> 2) & 3).  Sixteen
+// consecutive rows at one k-chunk then cover all 64 LDS banks exactly once.
+// Each stage is its own __shared__ array and the k-loop is unrolled by the number
+// of stages, so the compiler can tell the buffers apart and does not serialise the
+// LDS reads of one stage against the loads in flight for the others.
+#define BR_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define BR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+template <int BYTES, int S>
+__shared__ __attribute__((aligned(1024))) char g_stage[BYTES];
+
 template <int BM, int BN, int WGM, int WGN, int MODE, typename TOUT>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_dma_kernel(const bf16* __restrict__ A, int lda,
+                                                                      const bf16* __restrict__ W, int ldw, int M, int N,
+                                                                      int K, int tiles_m, int tiles_n, int group_n,
+                                                                      Epilogue<MODE, TOUT> epi) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int IA = BM / 16 / NW, IW = BN / 16 / NW;  // LDS-direct loads per wave and stage
+  constexpr int LPT = IA + IW;
+  constexpr int SA = BM * 64, STAGE = (BM + BN) * 64;   // bytes
+  static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile / wave mismatch");
+
+  const int nwg = tiles_m * tiles_n;
+  int wg = blockIdx.x;
+  {
+    const int per = nwg / 8, rem = nwg % 8, x = wg % 8, i = wg / 8;
+    wg = x * per + (x < rem ? x : rem) + i;
+  }
+  int tile_m, tile_n;
+  {
+    const int gsz = tiles_m * group_n;
+    const int g = wg / gsz, idx = wg - g * gsz;
+    const int gn = min(group_n, tiles_n - g * group_n);
+    tile_m = idx / gn;
+    tile_n = g * group_n + idx - tile_m * gn;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wv % WGM) * WTM, wn0 = (wv / WGM) * WTN;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  // global source of this lane for each of its loads (k advances by 32 per stage)
+  const bf16* ga[IA];
+  const bf16* gw[IW];
+#pragma unroll
+  for (int j = 0; j < IA; ++j) {
+    const int row = (wv * IA + j) * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
+    ga[j] = A + (size_t)min(m0 + row, M - 1) * lda + c * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < IW; ++j) {
+    const int row = (wv * IW + j) * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
+    gw[j] = W + (size_t)min(n0 + row, N - 1) * ldw + c * 8;
+  }
+  // byte offsets of this lane's operand fragments inside a stage, per k16 step
+  int fa_off[2][TM], fw_off[2][TN];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int row = wm0 + j * 32 + l32;
+      fa_off[ks][j] = row * 64 + (((ks * 2 + lh) ^ ((row >> 2) & 3)) << 4);
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      const int row = wn0 + i * 32 + l32;
+      fw_off[ks][i] = SA + row * 64 + (((ks * 2 + lh) ^ ((row >> 2) & 3)) << 4);
+    }
+  }
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / 32;
+  // The LDS-direct loads are issued from inline assembly: the compiler then does not
+  // see LDS being written and adds no waits of its own; completion is tracked here
+  // by hand.  Every step issues exactly LPT loads (past the end of K the last k-tile
+  // is fetched again into a stage nobody reads), so "at most 2*LPT loads outstanding"
+  // always means that the stage about to be multiplied has landed.
+  auto issue = [&](auto S, int kt) {
+    char* stage_ptr = g_stage<STAGE, decltype(S)::value>;
+    const unsigned base = (unsigned)(uintptr_t)BR_LPTR(stage_ptr);
+    const int kk = min(kt, nk - 1);
+#pragma unroll
+    for (int j = 0; j < IA; ++j) {
+      const bf16* src = ga[j] + (size_t)kk * 32;
+      const unsigned dst = base + (wv * IA + j) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+    }
+#pragma unroll
+    for (int j = 0; j < IW; ++j) {
+      const bf16* src = gw[j] + (size_t)kk * 32;
+      const unsigned dst = base + SA + (wv * IW + j) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+    }
+  };
+  // Operand fragments are prefetched one k16 half-step ahead: while the MFMAs of
+  // (kt, first half) run, the fragments of (kt, second half) are read; while those
+  // are multiplied, the first-half fragments of stage kt+1 are read.  The barrier
+  // sits between the two halves, where every wave still has MFMAs in flight.
+  bf16x8 fa0[TM], fw0[TN], fa1[TM], fw1[TN];
+  auto read_half = [&](const char* stage, int ks, bf16x8* a, bf16x8* w) {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) a[j] = *reinterpret_cast<const bf16x8*>(stage + fa_off[ks][j]);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) w[i] = *reinterpret_cast<const bf16x8*>(stage + fw_off[ks][i]);
+  };
+  auto mma_half = [&](const bf16x8* a, const bf16x8* w) {
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[i], a[j], acc[i][j], 0, 0, 0);
+  };
+  auto step = [&](auto S, int kt) {
+    constexpr int CUR = decltype(S)::value, NXT = (CUR + 1) & 3;
+    const char* cur = g_stage<STAGE, CUR>;
+    const char* nxt = g_stage<STAGE, NXT>;
+    read_half(cur, 1, fa1, fw1);
+    __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads ahead of the MFMAs they overlap with
+    mma_half(fa0, fw0);
+    __builtin_amdgcn_sched_barrier(0);  // ... and the MFMAs ahead of the barrier
+    // own loads of stage kt+1 landed (only the two younger stages may be outstanding)
+    // and both halves of stage kt are in registers -> barrier -> true for every wave:
+    // stage kt+1 may be read and stage kt may be refilled
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * LPT) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(std::integral_constant<int, CUR>{}, kt + 4);
+    read_half(nxt, 0, fa0, fw0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_half(fa1, fw1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+
+  issue(I0{}, 0);
+  issue(I1{}, 1);
+  issue(I2{}, 2);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  issue(I3{}, 3);
+  read_half(g_stage<STAGE, 0>, 0, fa0, fw0);
+  for (int kt = 0;; kt += 4) {
+    step(I0{}, kt);
+    if (kt + 1 >= nk) break;
+    step(I1{}, kt + 1);
+    if (kt + 2 >= nk) break;
+    step(I2{}, kt + 2);
+    if (kt + 3 >= nk) break;
+    step(I3{}, kt + 3);
+    if (kt + 4 >= nk) break;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the refills past the end of K
+
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = m0 + wm0 + j * 32 + l32;
+    if (m < M) {
+      const auto row = epi.row(m);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = n0 + wn0 + i * 32 + g * 8 + lh * 4;
+          if (n < N) epi.store(row, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, int MODE, typename TOUT>
+static br_status gemm_dma_launch(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
+                                 int group_n, hipStream_t st) {
+  Epilogue<MODE, TOUT> epi{ea};
+  const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
+  if (group_n <= 0 || group_n > tiles_n) group_n = tiles_n;
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<BM, BN, WGM, WGN, MODE, TOUT>), dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64),
+                     0, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, group_n, epi);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+template <int BM, int BN, int WGM, int WGN, int SWZ, int MODE, typename TOUT>
 static br_status gemm_launch(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
-                             hipStream_t st) {
+                             int group_n, hipStream_t st) {
   Epilogue<MODE, TOUT> epi{ea};
   const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
   const size_t lds = (size_t)2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, TOUT>;
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, SWZ, MODE, TOUT>;
+  if (group_n <= 0 || group_n > tiles_n) group_n = tiles_n;
   if (lds > 65536) {
     static bool attr_done = false;  // per instantiation
     if (!attr_done) {
@@ -165,28 +390,43 @@ static br_status gemm_launch(const bf16* A, int lda, const bf16* W, int ldw, int
     }
   }
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64), lds, st, A, lda, W, ldw, M, N, K, tiles_m,
-                     tiles_n, epi);
+                     tiles_n, group_n, epi);
   BR_LAUNCH_CHECK();
   return BR_OK;
 }
 
-// variant: 0 = 128x128 (4 waves), 1 = 256x128 (8 waves), 2 = 256x256 (8 waves), 3 = 128x256 (8 waves);
-// -1 = choose by problem size.
+// variant bits 0..3: tile shape, 0 = 128x128 (4 waves), 1 = 256x128 (8 waves), 2 = 256x256 (8 waves),
+// 3 = 128x256 (8 waves), 4 / 5 / 6 = 256x256 / 128x128 / 256x128 with LDS-direct loads and a four-stage
+// pipeline; bits 4..11: column-group width of the tile walk (0 = automatic);
+// bit 12: LDS swizzle by row instead of by row pair.  variant < 0 = choose everything by problem size.
 template <int MODE, typename TOUT>
 static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
                               int variant, hipStream_t st) {
+  int tile, group_n = 0, swz = 1;
   if (variant < 0) {
+    // measured on MI355X: the 256x256 LDS-direct kernel wins once it has enough tiles to fill
+    // the 256 compute units or the output is wide; otherwise 256x128 tiles
     const long long t256 = (long long)cdiv(M, 256) * cdiv(N, 256);
-    const long long t2561 = (long long)cdiv(M, 256) * cdiv(N, 128);
-    variant = t256 >= 512 ? 2 : (t2561 >= 512 ? 1 : 0);
+    tile = (t256 >= 400 || N >= 3072) ? 4 : 6;
+  } else {
+    tile = variant & 15;
+    group_n = (variant >> 4) & 255;
+    swz = (variant >> 12) & 1 ? 0 : 1;
   }
-  ProfScope ps(st, PROF_GEMM + MODE * 8 + variant, 2.0 * M * N * K);
-  switch (variant) {
-    case 0: return gemm_launch<128, 128, 2, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, st);
-    case 1: return gemm_launch<256, 128, 4, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, st);
-    case 2: return gemm_launch<256, 256, 2, 4, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, st);
-    case 3: return gemm_launch<128, 256, 2, 4, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, st);
+  ProfScope ps(st, PROF_GEMM + MODE * 8 + tile, 2.0 * M * N * K);
+#define BR_GEMM_CASE(BM_, BN_, WM_, WN_)                                                                          \
+  return swz ? gemm_launch<BM_, BN_, WM_, WN_, 1, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st)           \
+             : gemm_launch<BM_, BN_, WM_, WN_, 0, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st)
+  switch (tile) {
+    case 0: BR_GEMM_CASE(128, 128, 2, 2);
+    case 1: BR_GEMM_CASE(256, 128, 4, 2);
+    case 2: BR_GEMM_CASE(256, 256, 2, 4);
+    case 3: BR_GEMM_CASE(128, 256, 2, 4);
+    case 4: return gemm_dma_launch<256, 256, 2, 4, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case 5: return gemm_dma_launch<128, 128, 2, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case 6: return gemm_dma_launch<256, 128, 4, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
   }
+#undef BR_GEMM_CASE
   return fail(BR_EINVAL, "gemm: unknown variant");
 }
 
