@@ -118,7 +118,8 @@ typedef struct br_model br_model;
 /* Records the configuration and the BR_W_COUNT device pointers (not copied; they
  * must stay valid and 16-byte aligned while the model is used).
  * BR_ESHAPE unless: hidden % n_heads == 0; latent dims divisible by the patch;
- * D = latent_c*latent_t*latent_h*latent_w divisible by 4; head dim in
+ * D = latent_c*latent_t*latent_h*latent_w divisible by 4; hidden % 8 == 0,
+ * cond_dim % 8 == 0, pd % 4 == 0; head dim in
  * {16, 32, 64, 128} for BR_F32; for BR_BF16 additionally head dim in {64, 128},
  * hidden % 64 == 0, cond_dim % 64 == 0 and pd % 64 == 0. */
 br_status br_model_create(const br_model_cfg* cfg, const void* const* weight_ptrs, int32_t n_ptrs,

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbranchrollout.so")
-SOURCES = ["tree.cpp", "sde_kernels.hip", "tree_kernels.hip", "dit_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip",
+SOURCES = ["tree.cpp", "sde_kernels.hip", "tree_kernels.hip", "dit_kernels.hip", "gemm_bf16.hip", "gemm_bf16_stream.hip", "attn_bf16.hip",
            "forward.hip", "api.hip", "ops_api.hip", "prof.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -24,8 +24,13 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
+# per-file extras: keep the attention kernel's MFMA results in VGPRs (its softmax works on them
+# with ordinary vector instructions; accumulation registers would cost a copy per element)
+EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src, obj):
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "not a recognized feature" not in l)
     if r.returncode != 0:

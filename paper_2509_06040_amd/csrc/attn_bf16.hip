@@ -17,6 +17,7 @@ namespace br {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KV_TILE = 64;
 constexpr int VT_STRIDE = 68;  // bf16 elements per row of the transposed V tile (136 B)
@@ -27,8 +28,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   constexpr int CH = DH / 8;    // 16-byte chunks per K row
   constexpr int KS = DH / 16;   // MFMA k-steps of the score product
   constexpr int DB = DH / 32;   // 32-row blocks of O^T
-  __shared__ __attribute__((aligned(16))) uint4 sK[KV_TILE * CH];
-  __shared__ __attribute__((aligned(16))) bf16 sVt[DH * VT_STRIDE];
+  constexpr int NKC = KV_TILE * CH / 256;  // K chunks per thread and tile
+  constexpr int NVP = 32 * CH / 256;       // V key-pair items per thread and tile
+  __shared__ __attribute__((aligned(16))) u32x4 sK[2][KV_TILE * CH];
+  __shared__ __attribute__((aligned(16))) bf16 sVt[2][DH * VT_STRIDE];
 
   const int b = blockIdx.z, h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, lh = lane >> 5;
@@ -49,33 +52,53 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  const int nkv = (L + KV_TILE - 1) / KV_TILE;
-  for (int it = 0; it < nkv; ++it) {
-    const int k0 = it * KV_TILE;
-    __syncthreads();
-    // K tile: row-major, chunk c of row r in slot c ^ (r & 7)
+  // The next key/value tile is fetched into registers while the current one is multiplied
+  // out of LDS; two LDS buffers, one barrier per tile.
+  u32x4 rk[NKC];
+  bf16x8 rva[NVP], rvb[NVP];
+  auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < KV_TILE * CH / 256; ++i) {
+    for (int i = 0; i < NKC; ++i) {
       const int id = tid + i * 256, row = id / CH, c = id % CH;
       const int key = min(k0 + row, L - 1);
-      sK[row * CH + (c ^ (row & 7))] = *reinterpret_cast<const uint4*>(base + (size_t)key * ld + H + c * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(base + (size_t)key * ld + H + c * 8);
     }
-    // V tile transposed: a thread takes two neighbouring keys and one 8-wide d
-    // chunk and writes eight (key pair) words
 #pragma unroll
-    for (int i = 0; i < 32 * CH / 256; ++i) {
+    for (int i = 0; i < NVP; ++i) {
       const int id = tid + i * 256, p = id & 31, c = id >> 5;
       const int ka = min(k0 + 2 * p, L - 1), kb = min(k0 + 2 * p + 1, L - 1);
-      const bf16x8 va = *reinterpret_cast<const bf16x8*>(base + (size_t)ka * ld + 2 * H + c * 8);
-      const bf16x8 vb = *reinterpret_cast<const bf16x8*>(base + (size_t)kb * ld + 2 * H + c * 8);
+      rva[i] = *reinterpret_cast<const bf16x8*>(base + (size_t)ka * ld + 2 * H + c * 8);
+      rvb[i] = *reinterpret_cast<const bf16x8*>(base + (size_t)kb * ld + 2 * H + c * 8);
+    }
+  };
+  auto stash = [&](int buf) {
+    // K tile: row-major, chunk c of row r in slot c ^ (r & 7)
+#pragma unroll
+    for (int i = 0; i < NKC; ++i) {
+      const int id = tid + i * 256, row = id / CH, c = id % CH;
+      sK[buf][row * CH + (c ^ (row & 7))] = rk[i];
+    }
+    // V tile transposed: a thread holds two neighbouring keys of one 8-wide d chunk and
+    // writes eight (key pair) words
+#pragma unroll
+    for (int i = 0; i < NVP; ++i) {
+      const int id = tid + i * 256, p = id & 31, c = id >> 5;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        bf16x2 pr = {va[e], vb[e]};
-        *reinterpret_cast<bf16x2*>(&sVt[(c * 8 + e) * VT_STRIDE + 2 * p]) = pr;
+        bf16x2 pr = {rva[i][e], rvb[i][e]};
+        *reinterpret_cast<bf16x2*>(&sVt[buf][(c * 8 + e) * VT_STRIDE + 2 * p]) = pr;
       }
     }
-    __syncthreads();
+  };
+
+  const int nkv = (L + KV_TILE - 1) / KV_TILE;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int it = 0; it < nkv; ++it) {
+    const int k0 = it * KV_TILE, buf = it & 1;
+    if (it + 1 < nkv) fetch(k0 + KV_TILE);
 
     // S^T tile: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query l32
     f32x16 s[2];
@@ -87,38 +110,50 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int c = ks * 2 + lh;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[row * CH + (c ^ (row & 7))]);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][row * CH + (c ^ (row & 7))]);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
       }
     }
+    // keys past the end exist only in the last tile of a ragged sequence
+    if (k0 + KV_TILE > L) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (key >= L) s[kb][r] = -INFINITY;
+        }
+    }
+    // running maximum in the raw score domain (the scale is positive); the scale is folded
+    // into the exponent: p = exp2(s c - m c)
     float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-        const float v = key < L ? s[kb][r] * scale_log2 : -INFINITY;
-        s[kb][r] = v;
-        mx = fmaxf(mx, v);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float mc = m_new * scale_log2;
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
         s[kb][r] = p;
         psum += p;
       }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
+    // the accumulators are rescaled only when some query of this wave saw a new maximum
+    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
+      l_run *= alpha;
 #pragma unroll
-    for (int d = 0; d < DB; ++d)
+      for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      m_run = m_new;
+    }
+    l_run += psum;
 
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
 #pragma unroll
@@ -131,13 +166,16 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
         const int kofs = kb * 32 + j * 16 + lh * 4;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          const bf16* vr = &sVt[(d * 32 + l32) * VT_STRIDE + kofs];
+          const bf16* vr = &sVt[buf][(d * 32 + l32) * VT_STRIDE + kofs];
           const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vr);
           const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vr + 8);
           const bf16x8 vf = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
         }
       }
+    // the other buffer was last read one tile ago, before the previous barrier
+    if (it + 1 < nkv) stash(buf ^ 1);
+    __syncthreads();
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);

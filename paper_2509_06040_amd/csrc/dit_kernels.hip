@@ -57,32 +57,54 @@ __global__ __launch_bounds__(256) void cond_broadcast_kernel(const float* __rest
 }
 
 // ------------------------------------------------------- conditioning path
-// temb = [cos(1000 t f_k), sin(1000 t f_k)], f_k = 10000^(-k/128); pooled = mean of
-// the condition tokens.  Angles in fp64: 1000 t f is too large for fp32 sin/cos.
+// temb = [cos(1000 t f_k), sin(1000 t f_k)], f_k = 10000^(-k/128).  The angle (up to 1000 rad)
+// is formed and reduced to [-pi, pi] in fp64, then fp32 sin/cos suffice.
+__global__ __launch_bounds__(128) void temb_kernel(float t, float* __restrict__ temb) {
+  const int k = threadIdx.x;
+  const double f = exp(-9.210340371976184 * (double)k / 128.0);  // ln 10000
+  double a = 1000.0 * (double)t * f;
+  a -= 6.283185307179586 * rint(a * 0.15915494309189535);
+  float sn, cs;
+  sincosf((float)a, &sn, &cs);
+  temb[k] = cs;
+  temb[128 + k] = sn;
+}
+
+// pooled[c, :] = mean over the condition tokens of condition c (depends on the prompt only)
 template <typename T>
-__global__ __launch_bounds__(256) void temb_pool_kernel(float t, const T* __restrict__ cond, int n_cond, int Nc, int cd,
-                                                        float* __restrict__ temb, float* __restrict__ pooled) {
-  if (blockIdx.x == 0) {
-    for (int k = threadIdx.x; k < 128; k += 256) {
-      const double f = exp(-log(10000.0) * (double)k / 128.0);
-      const double a = 1000.0 * (double)t * f;
-      temb[k] = (float)cos(a);
-      temb[128 + k] = (float)sin(a);
-    }
-    return;
-  }
-  const int c = blockIdx.x - 1;
-  for (int d = threadIdx.x; d < cd; d += 256) {
-    float s = 0.f;
-    for (int j = 0; j < Nc; ++j) s += to_f(cond[((size_t)c * Nc + j) * cd + d]);
-    pooled[(size_t)c * cd + d] = s / (float)Nc;
-  }
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ cond, int Nc, int cd,
+                                                   float* __restrict__ pooled) {
+  const int c = blockIdx.y, d = blockIdx.x * 256 + threadIdx.x;
+  if (d >= cd) return;
+  float s = 0.f;
+  for (int j = 0; j < Nc; ++j) s += to_f(cond[((size_t)c * Nc + j) * cd + d]);
+  pooled[(size_t)c * cd + d] = s / (float)Nc;
 }
 
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
+template <typename TW>
+struct WChunk;  // eight consecutive weights as floats
+template <>
+struct WChunk<float> {
+  static __device__ inline void load(const float* p, float* w) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+  }
+};
+template <>
+struct WChunk<bf16> {
+  static __device__ inline void load(const bf16* p, float* w) {
+    typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+    const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e] = (float)v[e];
+  }
+};
+
 // out[r, n] = post( sum_k pre(in[r, k]) W[n, k] + bias[n] + add[n] ), r < R <= 8.
-// Weight-streaming: one wavefront per output column, lanes along k.
+// Weight-streaming: one wavefront per output column, lanes along k in 8-element chunks
+// (K % 8 == 0, rows 16-byte aligned).
 template <typename TW, int R>
 __global__ __launch_bounds__(256) void skinny_gemm_kernel(const float* __restrict__ in, int ldi,
                                                           const TW* __restrict__ W, int K, int N,
@@ -96,13 +118,19 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const float* __restric
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.f;
   const TW* wr = W + (size_t)n * K;
-  for (int k = lane; k < K; k += 64) {
-    const float w = to_f(wr[k]);
+  for (int k = lane * 8; k < K; k += 512) {
+    float w[8];
+    WChunk<TW>::load(wr + k, w);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      float a = in[(size_t)r * ldi + k];
-      if (pre_silu) a = silu_f(a);
-      acc[r] = fmaf(a, w, acc[r]);
+      const float4 a0 = *reinterpret_cast<const float4*>(in + (size_t)r * ldi + k);
+      const float4 a1 = *reinterpret_cast<const float4*>(in + (size_t)r * ldi + k + 4);
+      float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = pre_silu ? silu_f(a[e]) : a[e];
+        acc[r] = fmaf(x, w[e], acc[r]);
+      }
     }
   }
 #pragma unroll
@@ -147,8 +175,7 @@ template <typename T>
 static br_status conditioning_t(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond,
                                 hipStream_t st) {
   const int H = m->H;
-  hipLaunchKernelGGL((temb_pool_kernel<T>), dim3(1 + n_cond), dim3(256), 0, st, t, (const T*)cond, n_cond, m->Nc, m->cd,
-                     fb.temb, fb.pooled);
+  hipLaunchKernelGGL(temb_kernel, dim3(1), dim3(128), 0, st, t, fb.temb);
   BR_LAUNCH_CHECK();
   br_status s;
   if ((s = skinny<T>(fb.temb, 256, 1, (const T*)m->w[BR_W_T1_W], 256, H, (const float*)m->w[BR_W_T1_B], nullptr, 0, 1,
@@ -161,15 +188,26 @@ static br_status conditioning_t(const br_model* m, const FwdBuffers& fb, float t
                    0, fb.mods, m->A, st);
 }
 
+br_status launch_pool(const br_model* m, const FwdBuffers& fb, const void* cond, int n_cond, hipStream_t st) {
+  dim3 g(cdiv(m->cd, 256), n_cond), b(256);
+  if (m->cfg.dtype == BR_BF16)
+    hipLaunchKernelGGL((pool_kernel<bf16>), g, b, 0, st, (const bf16*)cond, m->Nc, m->cd, fb.pooled);
+  else
+    hipLaunchKernelGGL((pool_kernel<float>), g, b, 0, st, (const float*)cond, m->Nc, m->cd, fb.pooled);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
 br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st) {
   return m->cfg.dtype == BR_BF16 ? conditioning_t<bf16>(m, fb, t, cond, n_cond, st)
                                  : conditioning_t<float>(m, fb, t, cond, n_cond, st);
 }
 
 // ------------------------------------------------------- LayerNorm-modulate
-// out[r, :] = LN(x[src(r), :]) (1 + scale) + shift; one wavefront per row.
+// out[r, :] = LN(x[src(r), :]) (1 + scale) + shift; one wavefront per row, the row held in
+// registers (VPL float4 per lane; VPL = 0: any H, the row is re-read from cache instead).
 // r = b * rows_per_sample + tok, src = b * L_in + tok; LN without affine, eps 1e-6.
-template <typename T>
+template <typename T, int VPL>
 __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restrict__ x, T* __restrict__ out, int n_rows,
                                                           int rows_per_sample, int L_in, int H,
                                                           const float* __restrict__ mods, int A, int shift_off,
@@ -180,19 +218,36 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   const int b = r / rows_per_sample, tok = r - b * rows_per_sample;
   const float4* xr = reinterpret_cast<const float4*>(x + ((size_t)b * L_in + tok) * H);
   const int H4 = H >> 2;
+  float4 v[VPL > 0 ? VPL : 1];
   float s = 0.f;
-  for (int i = lane; i < H4; i += 64) {
-    const float4 v = xr[i];
-    s += (v.x + v.y) + (v.z + v.w);
+  if (VPL > 0) {
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      v[i] = xr[lane + 64 * i];
+      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  } else {
+    for (int i = lane; i < H4; i += 64) {
+      const float4 u = xr[i];
+      s += (u.x + u.y) + (u.z + u.w);
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   const float mean = s / (float)H;
   float q = 0.f;
-  for (int i = lane; i < H4; i += 64) {
-    const float4 v = xr[i];
-    const float a = v.x - mean, bq = v.y - mean, c = v.z - mean, d = v.w - mean;
-    q += (a * a + bq * bq) + (c * c + d * d);
+  if (VPL > 0) {
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      const float a = v[i].x - mean, bq = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+      q += (a * a + bq * bq) + (c * c + d * d);
+    }
+  } else {
+    for (int i = lane; i < H4; i += 64) {
+      const float4 u = xr[i];
+      const float a = u.x - mean, bq = u.y - mean, c = u.z - mean, d = u.w - mean;
+      q += (a * a + bq * bq) + (c * c + d * d);
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
@@ -201,11 +256,39 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   const float4* sh = reinterpret_cast<const float4*>(mrow + shift_off);
   const float4* sc = reinterpret_cast<const float4*>(mrow + scale_off);
   T* orow = out + (size_t)r * H;
-  for (int i = lane; i < H4; i += 64) {
-    const float4 v = xr[i], a = sh[i], g = sc[i];
-    store4<T>(orow + 4 * i, fmaf((v.x - mean) * rstd, 1.f + g.x, a.x), fmaf((v.y - mean) * rstd, 1.f + g.y, a.y),
-              fmaf((v.z - mean) * rstd, 1.f + g.z, a.z), fmaf((v.w - mean) * rstd, 1.f + g.w, a.w));
+  if (VPL > 0) {
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      const int c4 = lane + 64 * i;
+      const float4 a = sh[c4], g = sc[c4];
+      store4<T>(orow + 4 * c4, fmaf((v[i].x - mean) * rstd, 1.f + g.x, a.x), fmaf((v[i].y - mean) * rstd, 1.f + g.y, a.y),
+                fmaf((v[i].z - mean) * rstd, 1.f + g.z, a.z), fmaf((v[i].w - mean) * rstd, 1.f + g.w, a.w));
+    }
+  } else {
+    for (int i = lane; i < H4; i += 64) {
+      const float4 u = xr[i], a = sh[i], g = sc[i];
+      store4<T>(orow + 4 * i, fmaf((u.x - mean) * rstd, 1.f + g.x, a.x), fmaf((u.y - mean) * rstd, 1.f + g.y, a.y),
+                fmaf((u.z - mean) * rstd, 1.f + g.z, a.z), fmaf((u.w - mean) * rstd, 1.f + g.w, a.w));
+    }
   }
+}
+
+template <typename T>
+static void ln_launch(dim3 g, dim3 b, hipStream_t st, const float* x, T* out, int n_rows, int rows_per_sample, int L_in,
+                      int H, const float* mods, int A, int shift_off, int scale_off, const int* condmap) {
+#define BR_LN(V) hipLaunchKernelGGL((ln_modulate_kernel<T, V>), g, b, 0, st, x, out, n_rows, rows_per_sample, L_in, H, \
+                                    mods, A, shift_off, scale_off, condmap)
+  switch (H % 256 == 0 ? H / 256 : 0) {
+    case 1: BR_LN(1); break;
+    case 2: BR_LN(2); break;
+    case 3: BR_LN(3); break;
+    case 4: BR_LN(4); break;
+    case 6: BR_LN(6); break;
+    case 8: BR_LN(8); break;
+    case 12: BR_LN(12); break;
+    default: BR_LN(0); break;
+  }
+#undef BR_LN
 }
 
 br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, int rows_per_sample, int L_in, int H,
@@ -215,11 +298,9 @@ br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, i
   dim3 g(cdiv(n_rows, 4)), b(256);
   ProfScope ps(st, PROF_LN_MOD, (double)n_rows * H * (4.0 + (dtype == BR_BF16 ? 2.0 : 4.0)));
   if (dtype == BR_BF16)
-    hipLaunchKernelGGL((ln_modulate_kernel<bf16>), g, b, 0, st, x, (bf16*)out, n_rows, rows_per_sample, L_in, H, mods, A,
-                       shift_off, scale_off, condmap);
+    ln_launch<bf16>(g, b, st, x, (bf16*)out, n_rows, rows_per_sample, L_in, H, mods, A, shift_off, scale_off, condmap);
   else
-    hipLaunchKernelGGL((ln_modulate_kernel<float>), g, b, 0, st, x, (float*)out, n_rows, rows_per_sample, L_in, H, mods,
-                       A, shift_off, scale_off, condmap);
+    ln_launch<float>(g, b, st, x, (float*)out, n_rows, rows_per_sample, L_in, H, mods, A, shift_off, scale_off, condmap);
   BR_LAUNCH_CHECK();
   return BR_OK;
 }

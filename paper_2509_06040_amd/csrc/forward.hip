@@ -9,6 +9,7 @@ namespace br {
 br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st);
 br_status launch_patchify(const br_model* m, const FwdBuffers& fb, const float* z, int B, hipStream_t st);
 br_status launch_cond_broadcast(const br_model* m, const FwdBuffers& fb, int B, hipStream_t st);
+br_status launch_pool(const br_model* m, const FwdBuffers& fb, const void* cond, int n_cond, hipStream_t st);
 
 static size_t esize(const br_model* m) { return m->cfg.dtype == BR_BF16 ? 2 : 4; }
 
@@ -47,7 +48,8 @@ size_t plan_workspace(const br_model* m, int n_cond, int max_batch, long long v_
 }
 
 br_status embed_cond(const br_model* m, const FwdBuffers& fb, const void* cond_tokens, int n_cond, hipStream_t st) {
-  if (m->Nc == 0) return BR_OK;
+  br_status sp = launch_pool(m, fb, cond_tokens, n_cond, st);
+  if (sp != BR_OK) return sp;
   EpiArgs ea{};
   ea.bias = (const float*)m->w[BR_W_COND_B];
   ea.out = fb.cond_emb;
@@ -163,7 +165,8 @@ extern "C" br_status br_model_create(const br_model_cfg* cfg, const void* const*
   const long long D = (long long)c.latent_c * c.latent_t * c.latent_h * c.latent_w;
   const int pd = c.latent_c * c.patch_t * c.patch_h * c.patch_w, dh = c.hidden / c.n_heads;
   BR_REQUIRE(D % 4 == 0, BR_ESHAPE, "br_model_create: latent size must be a multiple of 4");
-  BR_REQUIRE(c.hidden % 4 == 0 && pd % 4 == 0, BR_ESHAPE, "br_model_create: hidden and patch dim must be multiples of 4");
+  BR_REQUIRE(c.hidden % 8 == 0 && c.cond_dim % 8 == 0 && pd % 4 == 0, BR_ESHAPE,
+             "br_model_create: hidden and cond_dim must be multiples of 8, patch dim of 4");
   if (c.dtype == BR_BF16) {
     BR_REQUIRE(dh == 64 || dh == 128, BR_ESHAPE, "br_model_create: bf16 head dim must be 64 or 128");
     BR_REQUIRE(c.hidden % 64 == 0 && c.cond_dim % 64 == 0 && pd % 64 == 0, BR_ESHAPE,

@@ -397,17 +397,18 @@ static br_status gemm_launch(const bf16* A, int lda, const bf16* W, int ldw, int
 
 // variant bits 0..3: tile shape, 0 = 128x128 (4 waves), 1 = 256x128 (8 waves), 2 = 256x256 (8 waves),
 // 3 = 128x256 (8 waves), 4 / 5 / 6 = 256x256 / 128x128 / 256x128 with LDS-direct loads and a four-stage
-// pipeline; bits 4..11: column-group width of the tile walk (0 = automatic);
+// pipeline, 7 = persistent 256x256 with a continuous operand stream (gemm_bf16_stream.hip); bits 4..11: column-group width of the tile walk (0 = automatic);
 // bit 12: LDS swizzle by row instead of by row pair.  variant < 0 = choose everything by problem size.
 template <int MODE, typename TOUT>
 static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
                               int variant, hipStream_t st) {
   int tile, group_n = 0, swz = 1;
   if (variant < 0) {
-    // measured on MI355X: the 256x256 LDS-direct kernel wins once it has enough tiles to fill
-    // the 256 compute units or the output is wide; otherwise 256x128 tiles
+    // measured on MI355X: the persistent 256x256 kernel wins once there are enough tiles to
+    // fill the 256 compute units or the output is wide; otherwise 256x128 tiles
     const long long t256 = (long long)cdiv(M, 256) * cdiv(N, 256);
-    tile = (t256 >= 400 || N >= 3072) ? 4 : 6;
+    const bool big = t256 >= 400 || N >= 3072;
+    tile = big ? (gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2) ? 7 : 4) : 6;
   } else {
     tile = variant & 15;
     group_n = (variant >> 4) & 255;
@@ -425,6 +426,7 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
     case 4: return gemm_dma_launch<256, 256, 2, 4, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 5: return gemm_dma_launch<128, 128, 2, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 6: return gemm_dma_launch<256, 128, 4, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case 7: return launch_gemm_bf16_stream(MODE, A, lda, W, ldw, M, N, K, ea, group_n, st);
   }
 #undef BR_GEMM_CASE
   return fail(BR_EINVAL, "gemm: unknown variant");

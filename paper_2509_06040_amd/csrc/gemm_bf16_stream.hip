@@ -1,0 +1,287 @@
+// Persistent bf16 GEMM for gfx950: C[m, n] = sum_k A[m, k] W[n, k], fp32 accumulate,
+// fused epilogue.  One workgroup per compute unit walks a list of 256x256 output
+// tiles; the operand stream (global memory -> LDS directly, 32-deep stages, a ring
+// of four) never stops at a tile boundary: while the last k-steps of a tile are
+// multiplied the first stages of the next tile are already being fetched, and they
+// keep landing while the finished tile goes through its epilogue.
+//
+// Epilogue: the MFMA accumulator layout gives a lane 4 consecutive columns of ONE
+// row, which would make every store instruction touch 32 different rows.  Each wave
+// therefore passes its accumulators through a private 4 KB LDS buffer, 16 rows at a
+// time (16-byte columns XOR-swizzled by the row, conflict-free both ways), and
+// writes rows of 64 consecutive columns: 16 lanes x 16 bytes per row.
+//
+// Requirements: K % 128 == 0 (every tile starts on ring slot 0), K >= 128.
+#include <type_traits>
+
+#include "common.h"
+#include "dit.h"
+
+namespace br {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define BR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+namespace {
+constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NW = 8;
+constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
+constexpr int IA = BM / 16 / NW, IW = BN / 16 / NW, LPT = IA + IW;  // LDS-direct loads per wave and stage
+constexpr int SA = BM * 64, STAGE = (BM + BN) * 64;                 // bytes
+}  // namespace
+
+template <int S>
+__shared__ __attribute__((aligned(1024))) char g_ring[STAGE];
+__shared__ __attribute__((aligned(1024))) char g_epi[NW * 4096];
+
+// Maps the j-th tile of workgroup `wg` to (tile_m, tile_n); false when the list is exhausted.
+// Consecutive workgroup ids are spread over the 8 XCDs, so XCD x = wg % 8 gets a contiguous
+// range of tiles, shared by its workgroups in round-robin; inside the range tiles are walked in
+// column groups of group_n with rows outermost, which keeps the group's weight panels in L2.
+__device__ inline bool stream_tile(int wg, int nwg, int j, int tiles_m, int tiles_n, int group_n, int* tm, int* tn) {
+  const int nt = tiles_m * tiles_n;
+  const int x = wg & 7, i = wg >> 3, per_x = (nwg - x + 7) >> 3;  // workgroups on this XCD
+  const int per = nt / 8, rem = nt % 8;
+  const int start = x * per + (x < rem ? x : rem), cnt = per + (x < rem ? 1 : 0);
+  const int local = i + j * per_x;
+  if (local >= cnt) return false;
+  const int t = start + local;
+  const int gsz = tiles_m * group_n;
+  const int g = t / gsz, idx = t - g * gsz;
+  const int gn = min(group_n, tiles_n - g * group_n);
+  *tm = idx / gn;
+  *tn = g * group_n + idx - (idx / gn) * gn;
+  return true;
+}
+
+template <int MODE, typename TOUT>
+__global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __restrict__ A, int lda,
+                                                               const bf16* __restrict__ W, int ldw, int M, int N, int K,
+                                                               int tiles_m, int tiles_n, int group_n,
+                                                               Epilogue<MODE, TOUT> epi) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wv % WGM) * WTM, wn0 = (wv / WGM) * WTN;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int nk = K / 32;
+
+  // byte offsets (from A / W) of this lane's sources, for the tile being multiplied and the next
+  unsigned oa[IA], ow[IW], oan[IA], own[IW];
+  auto tile_offsets = [&](int tm, int tn, unsigned* a, unsigned* w) {
+#pragma unroll
+    for (int j = 0; j < IA; ++j) {
+      const int row = (wv * IA + j) * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
+      a[j] = (unsigned)(((size_t)min(tm * BM + row, M - 1) * lda + c * 8) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < IW; ++j) {
+      const int row = (wv * IW + j) * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
+      w[j] = (unsigned)(((size_t)min(tn * BN + row, N - 1) * ldw + c * 8) * 2);
+    }
+  };
+  int fa_off[2][TM], fw_off[2][TN];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int row = wm0 + j * 32 + l32;
+      fa_off[ks][j] = row * 64 + (((ks * 2 + lh) ^ ((row >> 2) & 3)) << 4);
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      const int row = wn0 + i * 32 + l32;
+      fw_off[ks][i] = SA + row * 64 + (((ks * 2 + lh) ^ ((row >> 2) & 3)) << 4);
+    }
+  }
+
+  int tile_j = 0, tm = 0, tn = 0, tmn = 0, tnn = 0;
+  stream_tile(blockIdx.x, gridDim.x, 0, tiles_m, tiles_n, group_n, &tm, &tn);
+  bool has_next = stream_tile(blockIdx.x, gridDim.x, 1, tiles_m, tiles_n, group_n, &tmn, &tnn);
+  tile_offsets(tm, tn, oa, ow);
+  tile_offsets(has_next ? tmn : tm, has_next ? tnn : tn, oan, own);
+
+  // Stream element q of the current tile: k-slab q if q < nk, slab q - nk of the next tile
+  // otherwise (the last slab again when there is no next tile: a fetch nobody reads).
+  auto issue = [&](auto S, int q) {
+    char* ring = g_ring<decltype(S)::value>;
+    const unsigned base = (unsigned)(uintptr_t)BR_LPTR(ring);
+    const bool wrap = q >= nk && has_next;
+    const unsigned kb = (unsigned)(wrap ? q - nk : min(q, nk - 1)) * 64u;
+    const bf16* a_base = A;
+    const bf16* w_base = W;
+#pragma unroll
+    for (int j = 0; j < IA; ++j) {
+      const unsigned src = (wrap ? oan[j] : oa[j]) + kb;
+      const unsigned dst = base + (wv * IA + j) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(a_base) : "memory", "m0");
+    }
+#pragma unroll
+    for (int j = 0; j < IW; ++j) {
+      const unsigned src = (wrap ? own[j] : ow[j]) + kb;
+      const unsigned dst = base + SA + (wv * IW + j) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(w_base) : "memory", "m0");
+    }
+  };
+
+  f32x16 acc[TN][TM];
+  auto zero_acc = [&]() {
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  };
+  zero_acc();
+
+  bf16x8 fa0[TM], fw0[TN], fa1[TM], fw1[TN];
+  auto read_half = [&](const char* stage, int ks, bf16x8* a, bf16x8* w) {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) a[j] = *reinterpret_cast<const bf16x8*>(stage + fa_off[ks][j]);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) w[i] = *reinterpret_cast<const bf16x8*>(stage + fw_off[ks][i]);
+  };
+  // MFMAs of one half-step; `part` 0 / 1 selects the first / second weight fragment
+  // so that other work can be slotted between the two groups, -1 issues both
+  auto mma_half = [&](const bf16x8* a, const bf16x8* w, int part) {
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      if (part >= 0 && part != i) continue;
+#pragma unroll
+      for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[i], a[j], acc[i][j], 0, 0, 0);
+    }
+  };
+  // One k-step.  `drain`: first step after an epilogue, whose own loads and stores are mixed
+  // into the outstanding-operation count, so everything is waited for once.
+  auto step = [&](auto S, int kt, bool drain) {
+    constexpr int CUR = decltype(S)::value, NXT = (CUR + 1) & 3;
+    read_half(g_ring<CUR>, 1, fa1, fw1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_half(fa0, fw0, -1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * LPT) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(std::integral_constant<int, CUR>{}, kt + 4);
+    read_half(g_ring<NXT>, 0, fa0, fw0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_half(fa1, fw1, -1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+
+  issue(I0{}, 0);
+  issue(I1{}, 1);
+  issue(I2{}, 2);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  issue(I3{}, 3);
+  read_half(g_ring<0>, 0, fa0, fw0);
+
+  char* ebuf = g_epi + wv * 4096;
+  bool drain = false;
+  for (;;) {
+    for (int kt = 0; kt < nk; kt += 4) {
+      step(I0{}, kt, drain);
+      drain = false;
+      step(I1{}, kt + 1, false);
+      step(I2{}, kt + 2, false);
+      step(I3{}, kt + 3, false);
+    }
+    // ---- epilogue of tile (tm, tn); the next tile's first stages keep landing meanwhile
+    const int m_base = tm * BM + wm0, n_base = tn * BN + wn0;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        // rows 32 j + 16 p .. + 15 of this wave's sub-tile
+        if ((l32 >> 4) == p) {
+          const int r = l32 & 15;
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int c4 = i * 8 + g * 2 + lh;
+              f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+              *reinterpret_cast<f32x4*>(ebuf + r * 256 + ((c4 ^ r) << 4)) = v;
+            }
+        }
+        const int c4 = lane & 15;
+        const int n = n_base + c4 * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int r = (lane >> 4) + 4 * q;
+          const f32x4 v = *reinterpret_cast<const f32x4*>(ebuf + r * 256 + ((c4 ^ r) << 4));
+          const int m = m_base + j * 32 + p * 16 + r;
+          if (m < M && n < N) {
+            const auto row = epi.row(m);
+            epi.store(row, n, v[0], v[1], v[2], v[3]);
+          }
+        }
+      }
+    }
+    zero_acc();
+    if (!has_next) break;
+    tm = tmn;
+    tn = tnn;
+#pragma unroll
+    for (int j = 0; j < IA; ++j) oa[j] = oan[j];
+#pragma unroll
+    for (int j = 0; j < IW; ++j) ow[j] = own[j];
+    ++tile_j;
+    has_next = stream_tile(blockIdx.x, gridDim.x, tile_j + 1, tiles_m, tiles_n, group_n, &tmn, &tnn);
+    if (has_next) tile_offsets(tmn, tnn, oan, own);
+    drain = true;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the fetches past the end of the stream
+}
+
+template <int MODE, typename TOUT>
+static br_status stream_launch(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
+                               int group_n, hipStream_t st) {
+  Epilogue<MODE, TOUT> epi{ea};
+  const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
+  if (group_n <= 0 || group_n > tiles_n) group_n = tiles_n;
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    BR_HIP(hipGetDevice(&dev));
+    BR_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cu <= 0) n_cu = 256;
+  }
+  const int nt = tiles_m * tiles_n;
+  const int grid = nt < n_cu ? nt : n_cu;
+  hipLaunchKernelGGL((gemm_bf16_stream_kernel<MODE, TOUT>), dim3(grid), dim3(512), 0, st, A, lda, W, ldw, M, N, K,
+                     tiles_m, tiles_n, group_n, epi);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
+bool gemm_stream_supported(int M, int N, int K, size_t bytes_a, size_t bytes_w) {
+  // 32-bit byte offsets from the operand bases
+  return K >= 128 && K % 128 == 0 && bytes_a < (1ull << 32) && bytes_w < (1ull << 32);
+}
+
+br_status launch_gemm_bf16_stream(int mode, const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K,
+                                  const EpiArgs& ea, int group_n, hipStream_t st) {
+  BR_REQUIRE(gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2), BR_ESHAPE,
+             "streaming gemm: needs K % 128 == 0 and operands below 4 GiB");
+  switch (mode) {
+    case EPI_BIAS: return stream_launch<EPI_BIAS, bf16>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case EPI_BIAS_GELU: return stream_launch<EPI_BIAS_GELU, bf16>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case EPI_BIAS_GATE_RES: return stream_launch<EPI_BIAS_GATE_RES, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case EPI_PATCH_EMBED: return stream_launch<EPI_PATCH_EMBED, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case EPI_BIAS_F32: return stream_launch<EPI_BIAS_F32, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case EPI_UNPATCH: return stream_launch<EPI_UNPATCH, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+  }
+  return fail(BR_EINVAL, "gemm: unknown epilogue");
+}
+
+}  // namespace br

@@ -29,8 +29,8 @@ def test_gemm_fp32(lib, M, N, K):
     assert rel_l2(host(out), dit.gelu_tanh(ref)) < 1e-5
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 2 | (2 << 4) | (1 << 12), 4 | (3 << 4), -1])
-@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (129, 64, 64), (1101, 384, 128), (2 * 1101 + 5, 1024, 256), (700, 36, 192), (515, 640, 320)])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 7 | (2 << 4), 2 | (2 << 4) | (1 << 12), 4 | (3 << 4), -1])
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (129, 64, 64), (1101, 384, 128), (2 * 1101 + 5, 1024, 256), (700, 36, 192), (515, 640, 320), (5000, 4096, 128), (9000, 1280, 384)])
 def test_gemm_bf16_every_tile_shape(lib, variant, M, N, K):
     rng = np.random.default_rng(M + N)
     A, W = _bf(rng.standard_normal((M, K)).astype(np.float32)), _bf(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
@@ -38,6 +38,11 @@ def test_gemm_bf16_every_tile_shape(lib, variant, M, N, K):
     ref = A.astype(np.float64) @ W.astype(np.float64).T + b
     Ad, Wd = dev(A, torch.bfloat16), dev(W, torch.bfloat16)
     out32 = torch.full((M, N), -9.0, device=DEV)
+    if variant >= 0 and (variant & 15) == 7 and K % 128:
+        with pytest.raises(br.BranchRolloutError) as e:      # the streaming kernel needs K % 128 == 0
+            br.op_gemm(br.BF16, 4, Ad, Wd, dev(b), out32, variant=variant)
+        assert e.value.code == -3
+        return
     br.op_gemm(br.BF16, 4, Ad, Wd, dev(b), out32, variant=variant)
     assert rel_l2(host(out32), ref) < 1e-5, rel_l2(host(out32), ref)
     out16 = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
