@@ -80,11 +80,10 @@ br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, i
 
 // ---- epilogue device code, shared by the fp32 and the MFMA GEMM
 __device__ inline float gelu_tanh_f(float x) {
-  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  // tanh(u) = 1 - 2 / (exp(2u) + 1)
-  const float e = __expf(2.f * u);
-  const float th = 1.f - 2.f / (e + 1.f);
-  return 0.5f * x * (1.f + th);
+  // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3);
+  // exp(-2u) = exp2(x (k1 + k3 x^2)), k1 = -2 sqrt(2/pi) log2(e), k3 = 0.044715 k1
+  const float t = x * fmaf(x * x, -0.10294324f, -2.3022082f);
+  return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(t));
 }
 
 template <typename T>
@@ -127,6 +126,45 @@ struct Epilogue {
       r.o = (long long)m * a.ldo;
     }
     return r;
+  }
+  // rows per sample when the row mapping depends on the sample, else 0
+  __device__ inline int rows_per_sample() const {
+    return MODE == EPI_BIAS_GATE_RES ? a.L : (MODE == EPI_PATCH_EMBED || MODE == EPI_UNPATCH) ? a.n_img : 0;
+  }
+  // row(m) for a caller that already knows the sample b of row m and its token index
+  __device__ inline Row row_in_sample(int m, int b, int tok) const {
+    Row r;
+    r.aux = nullptr;
+    r.tok = tok;
+    if (MODE == EPI_BIAS_GATE_RES) {
+      r.o = (long long)m * a.ldo;
+      r.aux = a.mods + (size_t)a.condmap[b] * a.A + a.gate_off;
+    } else if (MODE == EPI_PATCH_EMBED) {
+      r.o = ((long long)b * a.L + tok) * a.ldo;
+      r.aux = a.pos + (size_t)tok * a.ldo;
+    } else if (MODE == EPI_UNPATCH) {
+      r.o = (long long)a.vrows[b] * a.D;
+    } else {
+      r.o = (long long)m * a.ldo;
+    }
+    return r;
+  }
+  // residual values x[m, n..n+3] of the gated-residual epilogue, for fetching ahead
+  __device__ inline float4 residual(int m, int n) const {
+    return *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.out) + (long long)m * a.ldo + n);
+  }
+  // store() with the residual already in registers (other modes ignore `pre`)
+  __device__ inline void store_pre(const Row& r, int n, float v0, float v1, float v2, float v3, const float4& pre) const {
+    if (MODE == EPI_BIAS_GATE_RES) {
+      const float4 bb = *reinterpret_cast<const float4*>(a.bias + n);
+      const float4 g = *reinterpret_cast<const float4*>(r.aux + n);
+      float4 xv;
+      xv.x = fmaf(g.x, v0 + bb.x, pre.x); xv.y = fmaf(g.y, v1 + bb.y, pre.y);
+      xv.z = fmaf(g.z, v2 + bb.z, pre.z); xv.w = fmaf(g.w, v3 + bb.w, pre.w);
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + r.o + n) = xv;
+    } else {
+      store(r, n, v0, v1, v2, v3);
+    }
   }
   // four consecutive output columns n..n+3 (n % 4 == 0)
   __device__ inline void store(const Row& r, int n, float v0, float v1, float v2, float v3) const {

@@ -14,6 +14,7 @@
 
 #include "common.h"
 #include "dit.h"
+#include "gemm_epilogue.h"
 #include "prof.h"
 
 namespace br {
@@ -344,21 +345,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_dma_kernel(const bf16
     if (kt + 4 >= nk) break;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the refills past the end of K
-
-#pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    const int m = m0 + wm0 + j * 32 + l32;
-    if (m < M) {
-      const auto row = epi.row(m);
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn0 + i * 32 + g * 8 + lh * 4;
-          if (n < N) epi.store(row, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-        }
-      }
-    }
+  __syncthreads();                                  // every wave is done with the stages
+  {
+    static_assert(STAGE >= 4 * 4096 && WTN == 64, "epilogue staging needs 4 KB per wave");
+    char* ebuf = (wv < 4 ? g_stage<STAGE, 0> : g_stage<STAGE, 1>)+(wv & 3) * 4096;
+    wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, m0 + wm0, n0 + wn0, M, N, epi, lane);
   }
 }
 
@@ -407,7 +398,7 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
     // measured on MI355X: the persistent 256x256 kernel wins once there are enough tiles to
     // fill the 256 compute units or the output is wide; otherwise 256x128 tiles
     const long long t256 = (long long)cdiv(M, 256) * cdiv(N, 256);
-    const bool big = t256 >= 400 || N >= 3072;
+    const bool big = t256 >= 200 || N >= 3072;
     tile = big ? (gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2) ? 7 : 4) : 6;
   } else {
     tile = variant & 15;

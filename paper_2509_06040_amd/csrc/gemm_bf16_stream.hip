@@ -16,6 +16,7 @@
 
 #include "common.h"
 #include "dit.h"
+#include "gemm_epilogue.h"
 
 namespace br {
 
@@ -196,37 +197,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
       step(I3{}, kt + 3, false);
     }
     // ---- epilogue of tile (tm, tn); the next tile's first stages keep landing meanwhile
-    const int m_base = tm * BM + wm0, n_base = tn * BN + wn0;
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-#pragma unroll
-      for (int p = 0; p < 2; ++p) {
-        // rows 32 j + 16 p .. + 15 of this wave's sub-tile
-        if ((l32 >> 4) == p) {
-          const int r = l32 & 15;
-#pragma unroll
-          for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const int c4 = i * 8 + g * 2 + lh;
-              f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-              *reinterpret_cast<f32x4*>(ebuf + r * 256 + ((c4 ^ r) << 4)) = v;
-            }
-        }
-        const int c4 = lane & 15;
-        const int n = n_base + c4 * 4;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int r = (lane >> 4) + 4 * q;
-          const f32x4 v = *reinterpret_cast<const f32x4*>(ebuf + r * 256 + ((c4 ^ r) << 4));
-          const int m = m_base + j * 32 + p * 16 + r;
-          if (m < M && n < N) {
-            const auto row = epi.row(m);
-            epi.store(row, n, v[0], v[1], v[2], v[3]);
-          }
-        }
-      }
-    }
+    wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, tm * BM + wm0, tn * BN + wn0, M, N, epi, lane);
     zero_acc();
     if (!has_next) break;
     tm = tmn;

@@ -59,7 +59,8 @@ __device__ inline void philox_normal4(const PhiloxKey& key, uint32_t quad, uint3
   for (int p = 0; p < 2; ++p) {
     const float ua = philox_uniform(w[2 * p]), ub = philox_uniform(w[2 * p + 1]);
     // -2 ln u = -2 ln2 * log2 u
-    const float r = __builtin_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(ua));
+    // hardware sqrt (1 ulp) without the denormal fix-up sequence: the argument is in [0, 34]
+    const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(ua));
     n[2 * p] = r * __builtin_amdgcn_cosf(ub);
     n[2 * p + 1] = r * __builtin_amdgcn_sinf(ub);
   }
