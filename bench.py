@@ -31,6 +31,29 @@ TILE_NAMES = {0: "128x128", 1: "256x128", 2: "256x256", 3: "128x256", 4: "256x25
               6: "256x128 lds-direct", 7: "256x256 persistent stream"}
 
 
+# HBM-side traffic per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch averaged over the launches of one step) scaled by what the same counters
+# read for a plain 1 GiB device copy (FETCH_SIZE reads 0.5 GiB -> x2.0; WRITE_SIZE reads 1 GiB -> x1.0);
+# see profiles/gemm_stream_hbm_traffic.md.  Valid only for the kernel sources hashed below.
+TRAFFIC = {
+    "gemm_bf16[bias_gate_residual,256x256 persistent stream]": dict(
+        bytes_per_launch=219877.28 * 1024 * 2.0 + 137219.37 * 1024 * 1.0,
+        sources=("gemm_bf16_stream.hip", "gemm_epilogue.h", "dit.h"), sha1="01fdce0b286d58032ad093575aa8df11aa2b3ef2"),
+}
+
+
+def measured_traffic(label):
+    """Counter-measured HBM bytes per launch, or None if the kernel changed since the counters were taken."""
+    import hashlib
+    t = TRAFFIC.get(label)
+    if t is None:
+        return None
+    h = hashlib.sha1()
+    for f in t["sources"]:
+        h.update(open(os.path.join(ROOT, "paper_2509_06040_amd", "csrc", f), "rb").read())
+    return round(t["bytes_per_launch"]) if h.hexdigest() == t["sha1"] else None
+
+
 def kernel_label(kid):
     if kid < 100:
         return "gemm_bf16[%s,%s]" % (GEMM_NAMES[kid // 8], TILE_NAMES[kid % 8])
@@ -48,6 +71,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time single launches in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (conditions are independent trees and would shard "
@@ -136,6 +161,13 @@ def main():
         phase_ms[name] = float(np.mean([e[0][a].elapsed_time(e[0][b]) for e in evs]))
     value = n_leaves / (ms_per_step * 1e-3)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- roofline of the dominant kernel (largest total time among the instrumented ones)
     kernels = {}
     for kid, (work, ms, cnt) in prof.items():
@@ -150,7 +182,7 @@ def main():
         dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
         k = kernels[dom]
         roofline = dict(kernel=dom, bound=k["bound"], achieved=k["achieved"], peak=PEAK_BF16_TFLOPS if k["bound"] == "mfma" else PEAK_HBM_GBS,
-                        unit=k["unit"], frac=k["frac"], traffic=None, avg_launch_us=k["avg_us"], launches=k["launches"])
+                        unit=k["unit"], frac=k["frac"], traffic=measured_traffic(dom), avg_launch_us=k["avg_us"], launches=k["launches"])
         mf = [v for v in kernels.values() if v["bound"] == "mfma"]
         tot_flop = sum(v["achieved"] * v["total_ms"] for v in mf)
         tot_ms = sum(v["total_ms"] for v in mf)

@@ -24,7 +24,7 @@ constexpr int VT_STRIDE = 68;  // bf16 elements per row of the transposed V tile
 
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
-                                                        int H, float scale_log2) {
+                                                        int H, int NH, int n_pairs, int grouped, float scale_log2) {
   constexpr int CH = DH / 8;    // 16-byte chunks per K row
   constexpr int KS = DH / 16;   // MFMA k-steps of the score product
   constexpr int DB = DH / 32;   // 32-row blocks of O^T
@@ -33,11 +33,26 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   __shared__ __attribute__((aligned(16))) u32x4 sK[2][KV_TILE * CH];
   __shared__ __attribute__((aligned(16))) bf16 sVt[2][DH * VT_STRIDE];
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  // Workgroups are dispatched round-robin over the 8 XCDs.  All query tiles of one
+  // (sample, head) read the same keys and values, so they are given to one XCD and run
+  // back to back there: K/V then come out of that XCD's L2 instead of being fetched 8 times.
+  const int nq = (L + 127) / 128;
+  // (With few pairs that would leave XCDs idle: then tiles are simply dealt out in order.)
+  int pair, qt;
+  if (grouped) {
+    const int x = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    pair = (slot / nq) * 8 + x;
+    qt = slot - (slot / nq) * nq;
+  } else {
+    pair = blockIdx.x / nq;
+    qt = blockIdx.x - pair * nq;
+  }
+  if (pair >= n_pairs) return;
+  const int b = pair / NH, h = pair - b * NH;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, lh = lane >> 5;
   const size_t ld = (size_t)3 * H;
   const bf16* base = qkv + (size_t)b * L * ld + (size_t)h * DH;
-  const int qi = blockIdx.x * 128 + wv * 32 + l32;
+  const int qi = qt * 128 + wv * 32 + l32;
   const int qc = min(qi, L - 1);
 
   bf16x8 qf[KS];
@@ -194,14 +209,17 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 }
 
 br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st) {
-  BR_REQUIRE(NH <= 65535 && B <= 65535, BR_ESHAPE, "attention: too many heads or samples for one launch");
   BR_REQUIRE(L >= 1, BR_EINVAL, "attention: empty sequence");
-  dim3 g(cdiv(L, 128), NH, B), blk(256);
+  const long long n_pairs = (long long)B * NH;
+  const int grouped = n_pairs >= 32 ? 1 : 0;
+  const long long n_blocks = (grouped ? (n_pairs + 7) / 8 * 8 : n_pairs) * cdiv(L, 128);
+  BR_REQUIRE(n_blocks <= 0x7FFFFFFFLL, BR_ESHAPE, "attention: too many workgroups for one launch");
+  dim3 g((unsigned)n_blocks), blk(256);
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)DH));
   const int H = NH * DH;
   ProfScope ps(st, PROF_ATTN + DH, 4.0 * B * (double)L * L * H);
-  if (DH == 64) hipLaunchKernelGGL((attn_bf16_kernel<64>), g, blk, 0, st, qkv, out, L, H, scale_log2);
-  else if (DH == 128) hipLaunchKernelGGL((attn_bf16_kernel<128>), g, blk, 0, st, qkv, out, L, H, scale_log2);
+  if (DH == 64) hipLaunchKernelGGL((attn_bf16_kernel<64>), g, blk, 0, st, qkv, out, L, H, NH, (int)n_pairs, grouped, scale_log2);
+  else if (DH == 128) hipLaunchKernelGGL((attn_bf16_kernel<128>), g, blk, 0, st, qkv, out, L, H, NH, (int)n_pairs, grouped, scale_log2);
   else return fail(BR_ESHAPE, "bf16 attention: head dim must be 64 or 128");
   BR_LAUNCH_CHECK();
   return BR_OK;
