@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, data-sheet figure
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 GEMM_NAMES = {0: "bias", 1: "bias_gelu", 2: "bias_gate_residual", 3: "patch_embed", 4: "bias_f32", 5: "unpatchify"}
-TILE_NAMES = {0: "128x128", 1: "256x128", 2: "256x256", 3: "128x256", 4: "256x256 lds-direct", 5: "128x128 lds-direct",
+TILE_NAMES = {4: "256x256 lds-direct", 5: "128x128 lds-direct",
               6: "256x128 lds-direct", 7: "256x256 persistent stream"}
 
 

@@ -169,3 +169,45 @@ def forward(cfg, W, z, t, cond, cond_index, act_round=identity, trace=None):
         o = xf @ W["final_w"].T + W["final_b"]
         out[b] = unpatchify(cfg, o[None])[0]
     return out
+
+
+def forward_rows(cfg, W, z, t, cond, cond_index, rows, act_round=identity):
+    """Velocity patches of selected image tokens for a ONE-block model: returns
+    [B, len(rows), patch_dim], the rows `rows` of final_lin's output (before
+    unpatchify).  With one block an output token depends on all tokens only through
+    the keys and values, so everything after the attention is evaluated on the
+    selected rows alone; used where the full forward is too slow on a CPU.
+    Pinned against forward() in tests/test_oracle_dit.py."""
+    assert cfg["n_blocks"] == 1
+    W = {k: np.asarray(v, dtype=np.float64) for k, v in W.items()}
+    z = np.asarray(z, dtype=np.float64)
+    cond = np.asarray(cond, dtype=np.float64)
+    rows = np.asarray(rows)
+    dm = dims(cfg)
+    H, nh, dh = cfg["hidden"], cfg["n_heads"], dm["d_head"]
+    _, mods = conditioning(cfg, W, t, cond)
+    cond_emb = act_round(cond) @ W["cond_w"].T + W["cond_b"]
+    patches = act_round(patchify(cfg, z))
+    out = np.empty((z.shape[0], len(rows), dm["patch_dim"]))
+    for b in range(z.shape[0]):
+        c = int(cond_index[b])
+        m = mods[c]
+        x = np.concatenate([patches[b] @ W["patch_w"].T + W["patch_b"] + W["pos"], cond_emb[c]], axis=0)
+        sh1, sc1, g1, sh2, sc2, g2 = (m[j * H:(j + 1) * H] for j in range(6))
+        xn = act_round(layer_norm(x) * (1.0 + sc1) + sh1)
+        kv = act_round(xn @ W["qkv_w"][0][H:].T + W["qkv_b"][0][H:])           # keys and values of all tokens
+        q = act_round(xn[rows] @ W["qkv_w"][0][:H].T + W["qkv_b"][0][:H])      # queries of the selected tokens
+        a = np.empty((len(rows), H))
+        for h in range(nh):
+            sl = slice(h * dh, (h + 1) * dh)
+            p = softmax_rows(q[:, sl] @ kv[:, :H][:, sl].T / np.sqrt(dh))
+            a[:, sl] = p @ kv[:, H:][:, sl]
+        a = act_round(a)
+        xr = x[rows] + g1 * (a @ W["proj_w"][0].T + W["proj_b"][0])
+        xn2 = act_round(layer_norm(xr) * (1.0 + sc2) + sh2)
+        hid = act_round(gelu_tanh(xn2 @ W["fc1_w"][0].T + W["fc1_b"][0]))
+        xr = xr + g2 * (hid @ W["fc2_w"][0].T + W["fc2_b"][0])
+        shf, scf = m[6 * H:7 * H], m[7 * H:8 * H]
+        xf = act_round(layer_norm(xr) * (1.0 + scf) + shf)
+        out[b] = xf @ W["final_w"].T + W["final_b"]
+    return out

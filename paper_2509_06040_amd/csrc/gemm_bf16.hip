@@ -1,15 +1,11 @@
 // bf16 GEMM on the gfx950 matrix cores: C[m, n] = sum_k A[m, k] W[n, k], fp32
 // accumulate, fused epilogue.  Both operands are k-contiguous, so a lane's MFMA
 // operand is one 16-byte LDS read.  The weights feed the MFMA row operand and the
-// activations the column operand: a lane then owns 4 consecutive output columns
-// of one output row, which makes the epilogue's bias / gate / residual accesses
-// and the stores 8- or 16-byte vectors.
+// activations the column operand (v_mfma_f32_32x32x16_bf16).
 //
-// Tile BM x BN x 64 per workgroup, WGM x WGN wavefronts, v_mfma_f32_32x32x16_bf16.
-// LDS rows are 128 bytes (eight 16-byte chunks); chunk c of row r sits in slot
-// c ^ (r & 7), which keeps both the staging writes and the operand reads free of
-// bank conflicts.  Global loads of tile k+1 are in flight while tile k is
-// multiplied; two LDS buffers, one barrier per k-step.
+// This file holds the one-tile-per-workgroup kernels (BM x BN tile, WGM x WGN
+// wavefronts) used for small problems and for K that is not a multiple of 128, and
+// the dispatch; the persistent kernel for large problems is in gemm_bf16_stream.hip.
 #include <type_traits>
 
 #include "common.h"
@@ -23,153 +19,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 // native vector type: arrays of HIP's uint4 struct are not promoted to registers
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-template <int BM, int BN, int WGM, int WGN, int SWZ, int MODE, typename TOUT>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16* __restrict__ A, int lda,
-                                                                  const bf16* __restrict__ W, int ldw, int M, int N,
-                                                                  int K, int tiles_m, int tiles_n, int group_n,
-                                                                  Epilogue<MODE, TOUT> epi) {
-  constexpr int NT = WGM * WGN * 64;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;
-  constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int CA = BM * 8 / NT, CW = BN * 8 / NT;  // 16-byte chunks per thread and tile
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile / thread mismatch");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  u32x4* sA = reinterpret_cast<u32x4*>(smem);                 // [2][BM * 8] chunks
-  u32x4* sW = sA + 2 * BM * 8;                                // [2][BN * 8] chunks
-
-  // Workgroup -> tile: consecutive workgroup ids go round-robin to the 8 XCDs, so
-  // give each XCD a contiguous range of tiles (n fastest): tiles that share an
-  // activation panel then share one L2.
-  const int nwg = tiles_m * tiles_n;
-  int wg = blockIdx.x;
-  {
-    const int per = nwg / 8, rem = nwg % 8, x = wg % 8, i = wg / 8;
-    // XCD x owns per (+1 if x < rem) tiles starting at x*per + min(x, rem)
-    wg = x * per + (x < rem ? x : rem) + i;
-  }
-  // inside an XCD's range tiles are walked in column groups of group_n tiles, rows
-  // outermost inside a group: the weight panels of a group stay in L2 while the
-  // activation panels stream through
-  int tile_m, tile_n;
-  {
-    const int gsz = tiles_m * group_n;
-    const int g = wg / gsz, idx = wg - g * gsz;
-    const int gn = min(group_n, tiles_n - g * group_n);
-    tile_m = idx / gn;
-    tile_n = g * group_n + idx - tile_m * gn;
-  }
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wm0 = (wv % WGM) * WTM, wn0 = (wv / WGM) * WTN;
-  const int l32 = lane & 31, lh = lane >> 5;
-
-  // staging: chunk id -> (row, k-chunk); rows beyond the matrix are clamped (their
-  // products are never stored)
-  const bf16* ga[CA];
-  const bf16* gw[CW];
-  int sa_off[CA], sw_off[CW];
-#pragma unroll
-  for (int i = 0; i < CA; ++i) {
-    const int id = tid + i * NT, row = id >> 3, c = id & 7;
-    const int gm = min(m0 + row, M - 1);
-    ga[i] = A + (size_t)gm * lda + c * 8;
-    sa_off[i] = row * 8 + (c ^ ((row >> SWZ) & 7));
-  }
-#pragma unroll
-  for (int i = 0; i < CW; ++i) {
-    const int id = tid + i * NT, row = id >> 3, c = id & 7;
-    const int gn = min(n0 + row, N - 1);
-    gw[i] = W + (size_t)gn * ldw + c * 8;
-    sw_off[i] = row * 8 + (c ^ ((row >> SWZ) & 7));
-  }
-
-  f32x16 acc[TN][TM];
-#pragma unroll
-  for (int i = 0; i < TN; ++i)
-#pragma unroll
-    for (int j = 0; j < TM; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  u32x4 ra[CA], rw[CW];
-  const int nk = K / 64;
-#pragma unroll
-  for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i]);
-#pragma unroll
-  for (int i = 0; i < CW; ++i) rw[i] = *reinterpret_cast<const u32x4*>(gw[i]);
-#pragma unroll
-  for (int i = 0; i < CA; ++i) sA[sa_off[i]] = ra[i];
-#pragma unroll
-  for (int i = 0; i < CW; ++i) sW[sw_off[i]] = rw[i];
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-#pragma unroll
-      for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + (size_t)(kt + 1) * 64);
-#pragma unroll
-      for (int i = 0; i < CW; ++i) rw[i] = *reinterpret_cast<const u32x4*>(gw[i] + (size_t)(kt + 1) * 64);
-    }
-    const u32x4* cA = sA + cur * BM * 8;
-    const u32x4* cW = sW + cur * BN * 8;
-    // operand fragments of k-step ks+1 are read while the MFMAs of step ks run
-    bf16x8 fa[2][TM], fw[2][TN];
-    auto read_frags = [&](int ks, bf16x8* a, bf16x8* w) {
-      const int c = ks * 2 + lh;
-#pragma unroll
-      for (int j = 0; j < TM; ++j) {
-        const int row = wm0 + j * 32 + l32;
-        a[j] = *reinterpret_cast<const bf16x8*>(&cA[row * 8 + (c ^ ((row >> SWZ) & 7))]);
-      }
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-        const int row = wn0 + i * 32 + l32;
-        w[i] = *reinterpret_cast<const bf16x8*>(&cW[row * 8 + (c ^ ((row >> SWZ) & 7))]);
-      }
-    };
-    read_frags(0, fa[0], fw[0]);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks + 1 < 4) read_frags(ks + 1, fa[(ks + 1) & 1], fw[(ks + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][i], fa[ks & 1][j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      u32x4* nA = sA + (cur ^ 1) * BM * 8;
-      u32x4* nW = sW + (cur ^ 1) * BN * 8;
-#pragma unroll
-      for (int i = 0; i < CA; ++i) nA[sa_off[i]] = ra[i];
-#pragma unroll
-      for (int i = 0; i < CW; ++i) nW[sw_off[i]] = rw[i];
-    }
-    __syncthreads();
-  }
-
-  // accumulator layout of the 32x32 MFMA: lane owns output row (= MFMA column)
-  // m = l32 and output columns n = 8 g + 4 lh + {0..3}, g = 0..3
-#pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    const int m = m0 + wm0 + j * 32 + l32;
-    if (m < M) {
-      const auto row = epi.row(m);
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn0 + i * 32 + g * 8 + lh * 4;
-          if (n < N) epi.store(row, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-        }
-      }
-    }
-  }
-}
-
 
 // ---------------------------------------------------------------------------
 // Deep-pipelined variant: operand tiles go from global memory straight into LDS
@@ -365,35 +214,13 @@ static br_status gemm_dma_launch(const bf16* A, int lda, const bf16* W, int ldw,
   return BR_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, int SWZ, int MODE, typename TOUT>
-static br_status gemm_launch(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
-                             int group_n, hipStream_t st) {
-  Epilogue<MODE, TOUT> epi{ea};
-  const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
-  const size_t lds = (size_t)2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, SWZ, MODE, TOUT>;
-  if (group_n <= 0 || group_n > tiles_n) group_n = tiles_n;
-  if (lds > 65536) {
-    static bool attr_done = false;  // per instantiation
-    if (!attr_done) {
-      BR_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      attr_done = true;
-    }
-  }
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64), lds, st, A, lda, W, ldw, M, N, K, tiles_m,
-                     tiles_n, group_n, epi);
-  BR_LAUNCH_CHECK();
-  return BR_OK;
-}
-
-// variant bits 0..3: tile shape, 0 = 128x128 (4 waves), 1 = 256x128 (8 waves), 2 = 256x256 (8 waves),
-// 3 = 128x256 (8 waves), 4 / 5 / 6 = 256x256 / 128x128 / 256x128 with LDS-direct loads and a four-stage
-// pipeline, 7 = persistent 256x256 with a continuous operand stream (gemm_bf16_stream.hip); bits 4..11: column-group width of the tile walk (0 = automatic);
-// bit 12: LDS swizzle by row instead of by row pair.  variant < 0 = choose everything by problem size.
+// variant bits 0..3: kernel, 4 / 5 / 6 = 256x256 / 128x128 / 256x128 tiles, one tile per workgroup, LDS-direct loads
+// in a four-stage ring; 7 = persistent 256x256 kernel with a continuous operand stream (gemm_bf16_stream.hip);
+// bits 4..11: column-group width of the tile walk (0 = all columns).  variant < 0 = choose by problem size.
 template <int MODE, typename TOUT>
 static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
                               int variant, hipStream_t st) {
-  int tile, group_n = 0, swz = 1;
+  int tile, group_n = 0;
   if (variant < 0) {
     // measured on MI355X: the persistent 256x256 kernel wins once there are enough tiles to
     // fill the 256 compute units or the output is wide; otherwise 256x128 tiles
@@ -403,23 +230,14 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
   } else {
     tile = variant & 15;
     group_n = (variant >> 4) & 255;
-    swz = (variant >> 12) & 1 ? 0 : 1;
   }
   ProfScope ps(st, PROF_GEMM + MODE * 8 + tile, 2.0 * M * N * K);
-#define BR_GEMM_CASE(BM_, BN_, WM_, WN_)                                                                          \
-  return swz ? gemm_launch<BM_, BN_, WM_, WN_, 1, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st)           \
-             : gemm_launch<BM_, BN_, WM_, WN_, 0, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st)
   switch (tile) {
-    case 0: BR_GEMM_CASE(128, 128, 2, 2);
-    case 1: BR_GEMM_CASE(256, 128, 4, 2);
-    case 2: BR_GEMM_CASE(256, 256, 2, 4);
-    case 3: BR_GEMM_CASE(128, 256, 2, 4);
     case 4: return gemm_dma_launch<256, 256, 2, 4, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 5: return gemm_dma_launch<128, 128, 2, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 6: return gemm_dma_launch<256, 128, 4, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 7: return launch_gemm_bf16_stream(MODE, A, lda, W, ldw, M, N, K, ea, group_n, st);
   }
-#undef BR_GEMM_CASE
   return fail(BR_EINVAL, "gemm: unknown variant");
 }
 

@@ -1,9 +1,15 @@
 // Persistent bf16 GEMM for gfx950: C[m, n] = sum_k A[m, k] W[n, k], fp32 accumulate,
 // fused epilogue.  One workgroup per compute unit walks a list of 256x256 output
-// tiles; the operand stream (global memory -> LDS directly, 32-deep stages, a ring
-// of four) never stops at a tile boundary: while the last k-steps of a tile are
-// multiplied the first stages of the next tile are already being fetched, and they
-// keep landing while the finished tile goes through its epilogue.
+// tiles; the operand stream (global memory -> LDS directly) never stops at a tile
+// boundary: while the last k-steps of a tile are multiplied the first stage of the
+// next tile is already being fetched, and it keeps landing while the finished tile
+// goes through its epilogue.
+//
+// Stages are 64 deep (128-byte row segments: measured 1.6x the L2->LDS throughput of
+// 64-byte segments on MI355X) and there are two of them; the refill of a stage is
+// issued three quarters of the way through the other one, right after the only
+// barrier of the stage.  Measured with the math in the loop, one 64 KB stage in
+// flight beats three 32 KB stages in flight.
 //
 // Epilogue: the MFMA accumulator layout gives a lane 4 consecutive columns of ONE
 // row, which would make every store instruction touch 32 different rows.  Each wave
@@ -11,7 +17,7 @@
 // time (16-byte columns XOR-swizzled by the row, conflict-free both ways), and
 // writes rows of 64 consecutive columns: 16 lanes x 16 bytes per row.
 //
-// Requirements: K % 128 == 0 (every tile starts on ring slot 0), K >= 128.
+// Requirements: K % 128 == 0 (every tile starts on ring slot 0), K >= 128, operands below 4 GiB.
 #include <type_traits>
 
 #include "common.h"
@@ -29,8 +35,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 namespace {
 constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NW = 8;
 constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
-constexpr int IA = BM / 16 / NW, IW = BN / 16 / NW, LPT = IA + IW;  // LDS-direct loads per wave and stage
-constexpr int SA = BM * 64, STAGE = (BM + BN) * 64;                 // bytes
+constexpr int BK = 64;                                              // k-depth of a stage
+constexpr int IA = BM / 8 / NW, IW = BN / 8 / NW, LPT = IA + IW;    // LDS-direct loads per wave and stage (8 rows each)
+constexpr int SA = BM * 128, STAGE = (BM + BN) * 128;               // bytes
 }  // namespace
 
 template <int S>
@@ -66,61 +73,55 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wv % WGM) * WTM, wn0 = (wv / WGM) * WTN;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int nk = K / 32;
+  const int nst = K / BK;  // stages per tile (even)
 
-  // byte offsets (from A / W) of this lane's sources, for the tile being multiplied and the next
-  unsigned oa[IA], ow[IW], oan[IA], own[IW];
-  auto tile_offsets = [&](int tm, int tn, unsigned* a, unsigned* w) {
-#pragma unroll
-    for (int j = 0; j < IA; ++j) {
-      const int row = (wv * IA + j) * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
-      a[j] = (unsigned)(((size_t)min(tm * BM + row, M - 1) * lda + c * 8) * 2);
-    }
-#pragma unroll
-    for (int j = 0; j < IW; ++j) {
-      const int row = (wv * IW + j) * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
-      w[j] = (unsigned)(((size_t)min(tn * BN + row, N - 1) * ldw + c * 8) * 2);
-    }
+  // A stage row is 128 bytes = eight 16-byte chunks; chunk c of row r sits in slot
+  // c ^ ((r >> 1) & 7): sixteen consecutive rows at one chunk index then cover all 64 LDS
+  // banks.  An LDS-direct load fills 8 consecutive rows (lane = 8 * row + slot), so the
+  // swizzle is applied to the global address the lane fetches from.
+  const int ld_row = lane >> 3;                                        // row inside an 8-row block
+  // all rows this lane ever loads have (row >> 1) & 7 == (ld_row >> 1) & 3 + 4 * (block & 1)
+  auto src_off = [&](int tile_row0, int blk, int limit, int ld) {
+    const int row = blk * 8 + ld_row;
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
+    return (unsigned)(((size_t)min(tile_row0 + row, limit - 1) * ld + c * 8) * 2);
   };
-  int fa_off[2][TM], fw_off[2][TN];
+  // fragment byte offsets inside a stage for k16-step 0; step ks is the same offset ^ (ks << 5)
+  int fa_off[TM], fw_off[TN];
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
+  for (int j = 0; j < TM; ++j) {
+    const int row = wm0 + j * 32 + l32;
+    fa_off[j] = row * 128 + ((lh ^ ((row >> 1) & 7)) << 4);
+  }
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
-      const int row = wm0 + j * 32 + l32;
-      fa_off[ks][j] = row * 64 + (((ks * 2 + lh) ^ ((row >> 2) & 3)) << 4);
-    }
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-      const int row = wn0 + i * 32 + l32;
-      fw_off[ks][i] = SA + row * 64 + (((ks * 2 + lh) ^ ((row >> 2) & 3)) << 4);
-    }
+  for (int i = 0; i < TN; ++i) {
+    const int row = wn0 + i * 32 + l32;
+    fw_off[i] = SA + row * 128 + ((lh ^ ((row >> 1) & 7)) << 4);
   }
 
   int tile_j = 0, tm = 0, tn = 0, tmn = 0, tnn = 0;
   stream_tile(blockIdx.x, gridDim.x, 0, tiles_m, tiles_n, group_n, &tm, &tn);
   bool has_next = stream_tile(blockIdx.x, gridDim.x, 1, tiles_m, tiles_n, group_n, &tmn, &tnn);
-  tile_offsets(tm, tn, oa, ow);
-  tile_offsets(has_next ? tmn : tm, has_next ? tnn : tn, oan, own);
 
-  // Stream element q of the current tile: k-slab q if q < nk, slab q - nk of the next tile
-  // otherwise (the last slab again when there is no next tile: a fetch nobody reads).
+  // Stream element q of the current tile: stage q if q < nst, stage q - nst of the next tile
+  // otherwise (the last stage again when there is no next tile: a fetch nobody reads).
   auto issue = [&](auto S, int q) {
     char* ring = g_ring<decltype(S)::value>;
     const unsigned base = (unsigned)(uintptr_t)BR_LPTR(ring);
-    const bool wrap = q >= nk && has_next;
-    const unsigned kb = (unsigned)(wrap ? q - nk : min(q, nk - 1)) * 64u;
+    const bool wrap = q >= nst && has_next;
+    const unsigned kb = (unsigned)(wrap ? q - nst : min(q, nst - 1)) * (BK * 2);
+    const int rm = (wrap ? tmn : tm) * BM, rn = (wrap ? tnn : tn) * BN;
     const bf16* a_base = A;
     const bf16* w_base = W;
 #pragma unroll
     for (int j = 0; j < IA; ++j) {
-      const unsigned src = (wrap ? oan[j] : oa[j]) + kb;
+      const unsigned src = src_off(rm, wv * IA + j, M, lda) + kb;
       const unsigned dst = base + (wv * IA + j) * 1024;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(a_base) : "memory", "m0");
     }
 #pragma unroll
     for (int j = 0; j < IW; ++j) {
-      const unsigned src = (wrap ? own[j] : ow[j]) + kb;
+      const unsigned src = src_off(rn, wv * IW + j, N, ldw) + kb;
       const unsigned dst = base + SA + (wv * IW + j) * 1024;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(w_base) : "memory", "m0");
     }
@@ -137,64 +138,59 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   };
   zero_acc();
 
-  bf16x8 fa0[TM], fw0[TN], fa1[TM], fw1[TN];
-  auto read_half = [&](const char* stage, int ks, bf16x8* a, bf16x8* w) {
+  // two fragment sets: set (ks & 1) holds k16-step ks
+  bf16x8 fa[2][TM], fw[2][TN];
+  auto read_frags = [&](const char* stage, int ks, int set) {
 #pragma unroll
-    for (int j = 0; j < TM; ++j) a[j] = *reinterpret_cast<const bf16x8*>(stage + fa_off[ks][j]);
+    for (int j = 0; j < TM; ++j) fa[set][j] = *reinterpret_cast<const bf16x8*>(stage + (fa_off[j] ^ (ks << 5)));
 #pragma unroll
-    for (int i = 0; i < TN; ++i) w[i] = *reinterpret_cast<const bf16x8*>(stage + fw_off[ks][i]);
+    for (int i = 0; i < TN; ++i) fw[set][i] = *reinterpret_cast<const bf16x8*>(stage + (fw_off[i] ^ (ks << 5)));
   };
-  // MFMAs of one half-step; `part` 0 / 1 selects the first / second weight fragment
-  // so that other work can be slotted between the two groups, -1 issues both
-  auto mma_half = [&](const bf16x8* a, const bf16x8* w, int part) {
+  auto mma = [&](int set) {
 #pragma unroll
-    for (int i = 0; i < TN; ++i) {
-      if (part >= 0 && part != i) continue;
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
-      for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[i], a[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < TM; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[set][i], fa[set][j], acc[i][j], 0, 0, 0);
+  };
+  // One stage = four k16-steps; the fragments of step ks+1 are read while step ks is multiplied.
+  // After the reads of the last step have been issued and have arrived, the other stage must
+  // have landed too (nothing younger is in flight); one barrier then makes both true for every
+  // wave, the freed stage is refilled, and the first fragments of the other stage are read.
+  auto stage_step = [&](auto S, int q) {
+    constexpr int CUR = decltype(S)::value, NXT = CUR ^ 1;
+    const char* cur = g_ring<CUR>;
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+      read_frags(cur, ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
-  };
-  // One k-step.  `drain`: first step after an epilogue, whose own loads and stores are mixed
-  // into the outstanding-operation count, so everything is waited for once.
-  auto step = [&](auto S, int kt, bool drain) {
-    constexpr int CUR = decltype(S)::value, NXT = (CUR + 1) & 3;
-    read_half(g_ring<CUR>, 1, fa1, fw1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_half(fa0, fw0, -1);
-    __builtin_amdgcn_sched_barrier(0);
-    if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * LPT) : "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue(std::integral_constant<int, CUR>{}, kt + 4);
-    read_half(g_ring<NXT>, 0, fa0, fw0);
+    issue(std::integral_constant<int, CUR>{}, q + 2);
+    read_frags(g_ring<NXT>, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    mma_half(fa1, fw1, -1);
+    mma(1);
     __builtin_amdgcn_sched_barrier(0);
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
-  using I2 = std::integral_constant<int, 2>;
-  using I3 = std::integral_constant<int, 3>;
 
   issue(I0{}, 0);
   issue(I1{}, 1);
-  issue(I2{}, 2);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  issue(I3{}, 3);
-  read_half(g_ring<0>, 0, fa0, fw0);
+  read_frags(g_ring<0>, 0, 0);
 
   char* ebuf = g_epi + wv * 4096;
-  bool drain = false;
   for (;;) {
-    for (int kt = 0; kt < nk; kt += 4) {
-      step(I0{}, kt, drain);
-      drain = false;
-      step(I1{}, kt + 1, false);
-      step(I2{}, kt + 2, false);
-      step(I3{}, kt + 3, false);
+    for (int q = 0; q < nst; q += 2) {
+      stage_step(I0{}, q);
+      stage_step(I1{}, q + 1);
     }
     // ---- epilogue of tile (tm, tn); the next tile's first stages keep landing meanwhile
     wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, tm * BM + wm0, tn * BN + wn0, M, N, epi, lane);
@@ -202,14 +198,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
     if (!has_next) break;
     tm = tmn;
     tn = tnn;
-#pragma unroll
-    for (int j = 0; j < IA; ++j) oa[j] = oan[j];
-#pragma unroll
-    for (int j = 0; j < IW; ++j) ow[j] = own[j];
     ++tile_j;
     has_next = stream_tile(blockIdx.x, gridDim.x, tile_j + 1, tiles_m, tiles_n, group_n, &tmn, &tnn);
-    if (has_next) tile_offsets(tmn, tnn, oan, own);
-    drain = true;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the fetches past the end of the stream
 }

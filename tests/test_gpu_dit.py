@@ -29,7 +29,7 @@ def test_gemm_fp32(lib, M, N, K):
     assert rel_l2(host(out), dit.gelu_tanh(ref)) < 1e-5
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 7 | (2 << 4), 2 | (2 << 4) | (1 << 12), 4 | (3 << 4), -1])
+@pytest.mark.parametrize("variant", [4, 5, 6, 7, 7 | (2 << 4), 4 | (3 << 4), 6 | (1 << 4), -1])
 @pytest.mark.parametrize("M,N,K", [(1, 128, 64), (129, 64, 64), (1101, 384, 128), (2 * 1101 + 5, 1024, 256), (700, 36, 192), (515, 640, 320), (5000, 4096, 128), (9000, 1280, 384)])
 def test_gemm_bf16_every_tile_shape(lib, variant, M, N, K):
     rng = np.random.default_rng(M + N)

@@ -129,3 +129,16 @@ def test_zero_gates_make_the_blocks_the_identity():
     a = dit.forward(cfg, W, z, 0.5, cond, [0])
     b = dit.forward(cfg, W2, z, 0.5, cond, [0])
     assert np.allclose(a, b, atol=1e-13)
+
+
+def test_row_subset_forward_equals_the_full_forward():
+    cfg = synth.model_cfg(1, 32, 4, (3, 2, 4, 6), (1, 2, 2), 5, synth.F32)
+    W = synth.make_weights(cfg, seed=8, std=0.2)
+    D = dit.dims(cfg)["D"]
+    z = synth.random_latents(2, D, 9).astype(np.float64)
+    cond = synth.cond_tokens(cfg, 2, seed=10).astype(np.float64)
+    rows = np.array([0, 3, 5, 11])
+    for rnd in (dit.identity, dit.round_bf16):
+        full = dit.patchify(cfg, dit.forward(cfg, W, z, 0.4, cond, [1, 0], act_round=rnd))
+        sub = dit.forward_rows(cfg, W, z, 0.4, cond, [1, 0], rows, act_round=rnd)
+        assert np.allclose(sub, full[:, rows], rtol=1e-11, atol=1e-13)
