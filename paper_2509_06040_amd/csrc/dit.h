@@ -131,39 +131,75 @@ struct Epilogue {
   __device__ inline int rows_per_sample() const {
     return MODE == EPI_BIAS_GATE_RES ? a.L : (MODE == EPI_PATCH_EMBED || MODE == EPI_UNPATCH) ? a.n_img : 0;
   }
-  // row(m) for a caller that already knows the sample b of row m and its token index
-  __device__ inline Row row_in_sample(int m, int b, int tok) const {
-    Row r;
-    r.aux = nullptr;
-    r.tok = tok;
-    if (MODE == EPI_BIAS_GATE_RES) {
-      r.o = (long long)m * a.ldo;
-      r.aux = a.mods + (size_t)a.condmap[b] * a.A + a.gate_off;
+  // ---- staged interface of the MFMA GEMM epilogue.  One hardware counter tracks a wave's
+  // loads and stores in issue order, so a load issued after a store cannot be waited for
+  // without also waiting for the store's write acknowledgement.  Whatever a tile's rows need
+  // from memory is therefore fetched ahead of the stores: column constants and per-sample
+  // constants once per tile, the per-row addend a few rows ahead.
+  struct SampleC {
+    float4 gate;  // gate[b, n..n+3] of the gated residual
+    long long o;  // output offset of the sample (patch embedding, unpatchify)
+  };
+  static constexpr bool kHasAddend = MODE == EPI_BIAS_GATE_RES || MODE == EPI_PATCH_EMBED;
+  __device__ inline float4 bias4(int n) const { return *reinterpret_cast<const float4*>(a.bias + n); }
+  __device__ inline SampleC sample_consts(int b, int n) const {
+    SampleC s;
+    s.gate = make_float4(0.f, 0.f, 0.f, 0.f);
+    s.o = 0;
+    if (MODE == EPI_BIAS_GATE_RES)
+      s.gate = *reinterpret_cast<const float4*>(a.mods + (size_t)a.condmap[b] * a.A + a.gate_off + n);
+    else if (MODE == EPI_PATCH_EMBED)
+      s.o = (long long)b * a.L * a.ldo;
+    else if (MODE == EPI_UNPATCH)
+      s.o = (long long)a.vrows[b] * a.D;
+    return s;
+  }
+  // what is added to row m (token tok of its sample) at columns n..n+3: the residual stream
+  // or the position embedding
+  __device__ inline float4 addend(int m, int tok, int n) const {
+    if (MODE == EPI_BIAS_GATE_RES)
+      return *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.out) + (long long)m * a.ldo + n);
+    if (MODE == EPI_PATCH_EMBED) return *reinterpret_cast<const float4*>(a.pos + (size_t)tok * a.ldo + n);
+    return make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // store() on operands already in registers
+  __device__ inline void finish(int m, int tok, int n, float v0, float v1, float v2, float v3, const float4& bb,
+                                const SampleC& sc, const float4& add) const {
+    v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
+    if (MODE == EPI_BIAS) {
+      store4<T>(reinterpret_cast<T*>(a.out) + (long long)m * a.ldo + n, v0, v1, v2, v3);
+    } else if (MODE == EPI_BIAS_GELU) {
+      store4<T>(reinterpret_cast<T*>(a.out) + (long long)m * a.ldo + n, gelu_tanh_f(v0), gelu_tanh_f(v1),
+                gelu_tanh_f(v2), gelu_tanh_f(v3));
+    } else if (MODE == EPI_BIAS_GATE_RES) {
+      store4<float>(reinterpret_cast<float*>(a.out) + (long long)m * a.ldo + n, fmaf(sc.gate.x, v0, add.x),
+                    fmaf(sc.gate.y, v1, add.y), fmaf(sc.gate.z, v2, add.z), fmaf(sc.gate.w, v3, add.w));
     } else if (MODE == EPI_PATCH_EMBED) {
-      r.o = ((long long)b * a.L + tok) * a.ldo;
-      r.aux = a.pos + (size_t)tok * a.ldo;
-    } else if (MODE == EPI_UNPATCH) {
-      r.o = (long long)a.vrows[b] * a.D;
+      store4<float>(reinterpret_cast<float*>(a.out) + sc.o + (long long)tok * a.ldo + n, v0 + add.x, v1 + add.y,
+                    v2 + add.z, v3 + add.w);
+    } else if (MODE == EPI_BIAS_F32) {
+      store4<float>(reinterpret_cast<float*>(a.out) + (long long)m * a.ldo + n, v0, v1, v2, v3);
     } else {
-      r.o = (long long)m * a.ldo;
+      Row r;
+      r.o = sc.o;
+      r.aux = nullptr;
+      r.tok = tok;
+      scatter_unpatch(r, n, v0, v1, v2, v3);
     }
-    return r;
   }
-  // residual values x[m, n..n+3] of the gated-residual epilogue, for fetching ahead
-  __device__ inline float4 residual(int m, int n) const {
-    return *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.out) + (long long)m * a.ldo + n);
-  }
-  // store() with the residual already in registers (other modes ignore `pre`)
-  __device__ inline void store_pre(const Row& r, int n, float v0, float v1, float v2, float v3, const float4& pre) const {
-    if (MODE == EPI_BIAS_GATE_RES) {
-      const float4 bb = *reinterpret_cast<const float4*>(a.bias + n);
-      const float4 g = *reinterpret_cast<const float4*>(r.aux + n);
-      float4 xv;
-      xv.x = fmaf(g.x, v0 + bb.x, pre.x); xv.y = fmaf(g.y, v1 + bb.y, pre.y);
-      xv.z = fmaf(g.z, v2 + bb.z, pre.z); xv.w = fmaf(g.w, v3 + bb.w, pre.w);
-      *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + r.o + n) = xv;
-    } else {
-      store(r, n, v0, v1, v2, v3);
+  // EPI_UNPATCH: token (tt, th, tw) raster, element (c, dt, dh, dw)
+  __device__ inline void scatter_unpatch(const Row& r, int n, float v0, float v1, float v2, float v3) const {
+    float* v = reinterpret_cast<float*>(a.out) + r.o;
+    const int tw = r.tok % a.gw, th = (r.tok / a.gw) % a.gh, tt = r.tok / (a.gw * a.gh);
+    const float vals[4] = {v0, v1, v2, v3};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int el = n + e;
+      const int dw = el % a.pw, dh = (el / a.pw) % a.ph, dt = (el / (a.pw * a.ph)) % a.pt,
+                c = el / (a.pw * a.ph * a.pt);
+      const long long idx =
+          (((long long)c * a.lt + tt * a.pt + dt) * a.lh + th * a.ph + dh) * a.lw + tw * a.pw + dw;
+      v[idx] = vals[e];
     }
   }
   // four consecutive output columns n..n+3 (n % 4 == 0)
@@ -186,19 +222,8 @@ struct Epilogue {
       store4<float>(reinterpret_cast<float*>(a.out) + r.o + n, v0 + p.x, v1 + p.y, v2 + p.z, v3 + p.w);
     } else if (MODE == EPI_BIAS_F32) {
       store4<float>(reinterpret_cast<float*>(a.out) + r.o + n, v0, v1, v2, v3);
-    } else {  // EPI_UNPATCH: token (tt, th, tw) raster, element (c, dt, dh, dw)
-      float* v = reinterpret_cast<float*>(a.out) + r.o;
-      const int tw = r.tok % a.gw, th = (r.tok / a.gw) % a.gh, tt = r.tok / (a.gw * a.gh);
-      const float vals[4] = {v0, v1, v2, v3};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int el = n + e;
-        const int dw = el % a.pw, dh = (el / a.pw) % a.ph, dt = (el / (a.pw * a.ph)) % a.pt,
-                  c = el / (a.pw * a.ph * a.pt);
-        const long long idx =
-            (((long long)c * a.lt + tt * a.pt + dt) * a.lh + th * a.ph + dh) * a.lw + tw * a.pw + dw;
-        v[idx] = vals[e];
-      }
+    } else {
+      scatter_unpatch(r, n, v0, v1, v2, v3);
     }
   }
 };

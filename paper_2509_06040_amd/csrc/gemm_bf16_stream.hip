@@ -38,6 +38,7 @@ constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
 constexpr int BK = 64;                                              // k-depth of a stage
 constexpr int IA = BM / 8 / NW, IW = BN / 8 / NW, LPT = IA + IW;    // LDS-direct loads per wave and stage (8 rows each)
 constexpr int SA = BM * 128, STAGE = (BM + BN) * 128;               // bytes
+constexpr int EPILOGUE_STORES = TM * 2 * 4;                         // store instructions of a full wave tile
 }  // namespace
 
 template <int S>
@@ -157,7 +158,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   // After the reads of the last step have been issued and have arrived, the other stage must
   // have landed too (nothing younger is in flight); one barrier then makes both true for every
   // wave, the freed stage is refilled, and the first fragments of the other stage are read.
-  auto stage_step = [&](auto S, int q) {
+  // `stores_behind`: the wave has issued at least EPILOGUE_STORES stores since the fetch of the
+  // other stage (the epilogue of a tile wholly inside the matrix).  Memory operations retire in
+  // issue order, so the other stage has landed once no more than that many are outstanding,
+  // and the stores' write acknowledgements need not be waited for yet.
+  auto stage_step = [&](auto S, int q, bool stores_behind) {
     constexpr int CUR = decltype(S)::value, NXT = CUR ^ 1;
     const char* cur = g_ring<CUR>;
 #pragma unroll
@@ -167,7 +172,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
       mma(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if (stores_behind)
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(EPILOGUE_STORES) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     issue(std::integral_constant<int, CUR>{}, q + 2);
@@ -187,15 +195,22 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   read_frags(g_ring<0>, 0, 0);
 
   char* ebuf = g_epi + wv * 4096;
+  bool stores_behind = false;
   for (;;) {
-    for (int q = 0; q < nst; q += 2) {
-      stage_step(I0{}, q);
-      stage_step(I1{}, q + 1);
+    stage_step(I0{}, 0, stores_behind);
+    stage_step(I1{}, 1, false);
+    for (int q = 2; q < nst; q += 2) {
+      stage_step(I0{}, q, false);
+      stage_step(I1{}, q + 1, false);
     }
     // ---- epilogue of tile (tm, tn); the next tile's first stages keep landing meanwhile
-    wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, tm * BM + wm0, tn * BN + wn0, M, N, epi, lane);
+    stores_behind = wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, tm * BM + wm0, tn * BN + wn0, M, N, epi, lane) >=
+                    EPILOGUE_STORES;
     zero_acc();
     if (!has_next) break;
+    // read the next tile's first fragments again rather than keep them alive across the
+    // epilogue, which needs the registers for the rows it fetches ahead
+    read_frags(g_ring<0>, 0, 0);
     tm = tmn;
     tn = tnn;
     ++tile_j;
