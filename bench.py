@@ -34,11 +34,23 @@ TILE_NAMES = {4: "256x256 lds-direct", 5: "128x128 lds-direct",
 # HBM-side traffic per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE, KiB per dispatch averaged over the launches of one step) scaled by what the same counters
 # read for a plain 1 GiB device copy (FETCH_SIZE reads 0.5 GiB -> x2.0; WRITE_SIZE reads 1 GiB -> x1.0);
-# see profiles/gemm_stream_hbm_traffic.md.  Valid only for the kernel sources hashed below.
+# see profiles/hot_kernels_hbm_traffic.md.  Valid only for the kernel sources hashed below.
 TRAFFIC = {
     "gemm_bf16[bias_gate_residual,256x256 persistent stream]": dict(
-        bytes_per_launch=219877.28 * 1024 * 2.0 + 137219.37 * 1024 * 1.0,
-        sources=("gemm_bf16_stream.hip", "gemm_epilogue.h", "dit.h"), sha1="01fdce0b286d58032ad093575aa8df11aa2b3ef2"),
+        bytes_per_launch=224710.92 * 1024 * 2.0 + 141827.37 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="de8d88c86c9407b27feccfa8b52333a2770309ca"),
+    "gemm_bf16[bias_gelu,256x256 persistent stream]": dict(
+        bytes_per_launch=230884.75 * 1024 * 2.0 + 174528.00 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="de8d88c86c9407b27feccfa8b52333a2770309ca"),
+    "gemm_bf16[bias,256x256 persistent stream]": dict(
+        bytes_per_launch=166943.22 * 1024 * 2.0 + 131145.78 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="de8d88c86c9407b27feccfa8b52333a2770309ca"),
+    "attn_bf16[d64]": dict(
+        bytes_per_launch=63429.41 * 1024 * 2.0 + 42082.67 * 1024 * 1.0,
+        sources=('attn_bf16.hip',), sha1="e6eb6aa414965f25529e7043744ae0f8131c2743"),
+    "ln_modulate": dict(
+        bytes_per_launch=42116.92 * 1024 * 2.0 + 41964.94 * 1024 * 1.0,
+        sources=('dit_kernels.hip',), sha1="7fc6453ed298939f548883bec24304ec782964b2"),
 }
 
 
