@@ -66,24 +66,50 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const bf16x2 one2 = {(bf16)1.0f, (bf16)1.0f};
 
   // The next key/value tile is fetched into registers while the current one is multiplied
   // out of LDS; two LDS buffers, one barrier per tile.
   u32x4 rk[NKC];
   bf16x8 rva[NVP], rvb[NVP];
+  // byte offsets of this thread's items from the first key of a tile; a tile's base address is
+  // uniform, so a fetch is a scalar base plus these 32-bit offsets
+  const unsigned ldb = (unsigned)(ld * 2);
+  unsigned koff[NKC], voff[NVP];
+#pragma unroll
+  for (int i = 0; i < NKC; ++i) {
+    const int id = tid + i * 256, row = id / CH, c = id % CH;
+    koff[i] = row * ldb + (H + c * 8) * 2;
+  }
+#pragma unroll
+  for (int i = 0; i < NVP; ++i) {
+    const int id = tid + i * 256, p = id & 31, c = id >> 5;
+    voff[i] = 2 * p * ldb + (2 * H + c * 8) * 2;
+  }
   auto fetch = [&](int k0) {
+    const char* tile = reinterpret_cast<const char*>(base) + (size_t)k0 * ldb;
+    if (k0 + KV_TILE <= L) {
 #pragma unroll
-    for (int i = 0; i < NKC; ++i) {
-      const int id = tid + i * 256, row = id / CH, c = id % CH;
-      const int key = min(k0 + row, L - 1);
-      rk[i] = *reinterpret_cast<const u32x4*>(base + (size_t)key * ld + H + c * 8);
-    }
+      for (int i = 0; i < NKC; ++i) rk[i] = *reinterpret_cast<const u32x4*>(tile + koff[i]);
 #pragma unroll
-    for (int i = 0; i < NVP; ++i) {
-      const int id = tid + i * 256, p = id & 31, c = id >> 5;
-      const int ka = min(k0 + 2 * p, L - 1), kb = min(k0 + 2 * p + 1, L - 1);
-      rva[i] = *reinterpret_cast<const bf16x8*>(base + (size_t)ka * ld + 2 * H + c * 8);
-      rvb[i] = *reinterpret_cast<const bf16x8*>(base + (size_t)kb * ld + 2 * H + c * 8);
+      for (int i = 0; i < NVP; ++i) {
+        rva[i] = *reinterpret_cast<const bf16x8*>(tile + voff[i]);
+        rvb[i] = *reinterpret_cast<const bf16x8*>(tile + voff[i] + ldb);
+      }
+    } else {  // ragged last tile: keys past the end read the last key (their scores are masked)
+      const int last = L - 1 - k0;
+#pragma unroll
+      for (int i = 0; i < NKC; ++i) {
+        const int id = tid + i * 256, row = id / CH, c = id % CH;
+        rk[i] = *reinterpret_cast<const u32x4*>(tile + min(row, last) * ldb + (H + c * 8) * 2);
+      }
+#pragma unroll
+      for (int i = 0; i < NVP; ++i) {
+        const int id = tid + i * 256, p = id & 31, c = id >> 5;
+        rva[i] = *reinterpret_cast<const bf16x8*>(tile + min(2 * p, last) * ldb + (2 * H + c * 8) * 2);
+        rvb[i] = *reinterpret_cast<const bf16x8*>(tile + min(2 * p + 1, last) * ldb + (2 * H + c * 8) * 2);
+      }
     }
   };
   auto stash = [&](int buf) {
@@ -111,6 +137,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   fetch(0);
   stash(0);
   __syncthreads();
+  // Pin the query fragments in registers here.  Left alone, the compiler sinks their loads to
+  // just before the loop, and its wait-count bookkeeping at the loop header then makes every
+  // iteration wait for the key/value fetch it has just issued.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   for (int it = 0; it < nkv; ++it) {
     const int k0 = it * KV_TILE, buf = it & 1;
     if (it + 1 < nkv) fetch(k0 + KV_TILE);
@@ -149,15 +180,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
     const float mc = m_new * scale_log2;
-    float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
-        s[kb][r] = p;
-        psum += p;
-      }
+      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
     // the accumulators are rescaled only when some query of this wave saw a new maximum
     if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
@@ -168,7 +194,6 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
         for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
       m_run = m_new;
     }
-    l_run += psum;
 
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
 #pragma unroll
@@ -178,6 +203,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[kb][8 * j + e];
+        // row sum of the rounded probabilities, two per instruction (what the product below sums)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const bf16x2 pr = {pf[e], pf[e + 1]};
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_run, false);
+        }
         const int kofs = kb * 32 + j * 16 + lh * 4;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {

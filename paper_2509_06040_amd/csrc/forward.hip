@@ -4,6 +4,7 @@
 #include "common.h"
 #include "dit.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace br {
 br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st);
@@ -78,6 +79,8 @@ br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, 
   }
   BR_TRY(launch_cond_broadcast(m, fb, B, st));
   const int M = B * L;
+  // the bf16 block stack launches only instrumented kernels, back to back
+  ProfChain chain(dt == BR_BF16);
   for (int k = 0; k < m->NB; ++k) {
     const int mo = k * 6 * H;
     const char* qkv_w = (const char*)m->w[BR_W_QKV_W] + (size_t)k * 3 * H * H * es;

@@ -13,8 +13,12 @@ struct Rec {
   int id;
   double work;
   hipEvent_t a, b;
+  bool shared_a;  // `a` is the previous record's `b`
 };
 bool g_on = false;
+bool g_chain = false;
+hipEvent_t g_chain_prev = nullptr;  // closing event of the last launch of the running chain
+hipStream_t g_chain_stream = nullptr;
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 hipEvent_t get_event() {
@@ -30,12 +34,23 @@ hipEvent_t get_event() {
 }  // namespace
 
 bool prof_on() { return g_on; }
+void prof_chain(bool on) {
+  g_chain = on;
+  g_chain_prev = nullptr;
+}
 void prof_begin(hipStream_t st, int id, double work) {
-  Rec r{id, work, get_event(), get_event()};
-  (void)hipEventRecord(r.a, st);
+  const bool share = g_chain && g_chain_prev != nullptr && g_chain_stream == st;
+  Rec r{id, work, share ? g_chain_prev : get_event(), get_event(), share};
+  if (!share) (void)hipEventRecord(r.a, st);
   g_recs.push_back(r);
 }
-void prof_end(hipStream_t st) { (void)hipEventRecord(g_recs.back().b, st); }
+void prof_end(hipStream_t st) {
+  (void)hipEventRecord(g_recs.back().b, st);
+  if (g_chain) {
+    g_chain_prev = g_recs.back().b;
+    g_chain_stream = st;
+  }
+}
 }  // namespace br
 
 using namespace br;
@@ -57,7 +72,7 @@ extern "C" br_status br_profile_read(int32_t max_ids, int32_t* ids, double* work
     a.first.first += r.work;
     a.first.second += t;
     a.second += 1;
-    g_pool.push_back(r.a);
+    if (!r.shared_a) g_pool.push_back(r.a);
     g_pool.push_back(r.b);
   }
   g_recs.clear();

@@ -13,6 +13,18 @@ enum ProfId {
 bool prof_on();
 void prof_begin(hipStream_t st, int id, double work);  // work: flops or bytes of this launch
 void prof_end(hipStream_t st);
+// Inside a chain every launch on the stream is an instrumented one, back to back: the event
+// that closes one launch also opens the next, which halves the events put between kernels.
+void prof_chain(bool on);
+struct ProfChain {
+  bool on;
+  explicit ProfChain(bool enable) : on(enable && prof_on()) {
+    if (on) prof_chain(true);
+  }
+  ~ProfChain() {
+    if (on) prof_chain(false);
+  }
+};
 struct ProfScope {
   hipStream_t st;
   bool on;
