@@ -237,10 +237,19 @@ br_status br_leaf_reward(const br_tree* tree, const float* z_nodes, int32_t kind
 /* Clipped GRPO objective value over a set of edges (Eq. 5):
  *   J = 1/n sum_e min(rho_e A_e, clip(rho_e, 1-clip_eps, 1+clip_eps) A_e),
  *   rho_e = exp(logp_new[e] - logp_old_nodes[edge_ids[e]]), A_e = adv_nodes[edge_ids[e]].
- *   edge_ids dev [n_edges]; logp_new dev [n_edges]; J dev out [1] (0 if n_edges = 0). */
+ *   edge_ids dev [n_edges]; logp_new dev [n_edges]; J dev out [1] (0 if n_edges = 0);
+ *   clipped dev out [n_edges] or NULL: 1 where the clipped term is the smaller one (the edge
+ *   then contributes no gradient), else 0. */
 br_status br_grpo_objective(const float* logp_new, const float* logp_old_nodes, const float* adv_nodes,
                             const int32_t* edge_ids, int32_t n_edges, float clip_eps, float* J,
-                            void* stream);
+                            uint8_t* clipped, void* stream);
+
+/* Effective sample size of the fusion weights (appendix on the self-normalised importance
+ * sampling view of Eq. 3): ESS(n) = (sum_l w_l)^2 / sum_l w_l^2 over the leaves l under node n
+ * with the weights of Eq. 3 (1 for a leaf, the number of leaves under n for uniform weights).
+ *   logp_edges dev [n_tree*n_nodes]; ess_nodes dev out [n_tree*n_nodes]. */
+br_status br_fusion_ess(const br_tree* tree, const float* logp_edges, float beta, float* ess_nodes,
+                        void* stream);
 
 /* Velocity of a batch at one time (the network alone; used for teacher-forced
  * checks).  z dev [B, D] fp32; cond_index host [B] -> row of cond_tokens
@@ -275,6 +284,14 @@ br_status br_noise_stream(uint64_t seed, uint32_t node_id, uint32_t step, uint32
 br_status br_depth_mask_window(int32_t T, int32_t last_split, int32_t window, int32_t iter,
                                int32_t every, int32_t stop, uint8_t* mask_out);
 br_status br_depth_mask_seeded(int32_t T, int32_t n_drop, uint64_t seed, uint8_t* mask_out);
+
+/* Hybrid ODE-SDE schedule (ablation "Hybrid ODE-SDE"): every split step stays an SDE step, the
+ * steps of a sliding window (window_mask[i] != 0, e.g. from br_depth_mask_window) too, all
+ * other steps become deterministic.  sigma_out[i] = eta on SDE steps, 0 on ODE steps;
+ * ode_mask_out[i] = 1 on ODE steps -- OR it into the depth mask of br_prune so that the edges
+ * of ODE steps, which carry no log-probability, stay out of the update.  Host memory only. */
+br_status br_mix_schedule(int32_t T, const int32_t* split_steps, int32_t n_splits, const uint8_t* window_mask,
+                          float eta, float* sigma_out, uint8_t* ode_mask_out);
 
 #ifdef __cplusplus
 }

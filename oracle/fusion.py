@@ -68,3 +68,27 @@ def depth_advantages(tree, rbar, n_cond, eps=1e-8, ddof=0, a_max=5.0):
                 a = np.clip(a, -a_max, a_max)
             adv[c, lo:hi] = a
     return adv.reshape(-1)
+
+
+def ess(tree, logp_edges, beta, n_tree):
+    """Effective sample size of the fusion weights of every node (appendix, self-normalised
+    importance sampling view of Eq. 3): with w_l the Eq. 3 weights of the leaves under node n,
+    ESS(n) = (sum_l w_l)^2 / sum_l w_l^2.  -> float64 [n_tree*n_nodes]."""
+    n_nodes, T = tree["n_nodes"], tree["T"]
+    parent, leaf_lo, leaf_hi = tree["parent"], tree["leaf_lo"], tree["leaf_hi"]
+    leaf0 = tree["off"][T]
+    lp = np.asarray(logp_edges, np.float64).reshape(n_tree, n_nodes)
+    out = np.zeros((n_tree, n_nodes))
+    for c in range(n_tree):
+        for n in range(n_nodes):
+            s = []
+            for l in range(leaf_lo[n], leaf_hi[n]):
+                acc, m = 0.0, leaf0 + l
+                while m != n:                 # log-probs of the edges on the path n -> leaf
+                    acc += lp[c, m]
+                    m = parent[m]
+                s.append(beta * acc)
+            s = np.array(s)
+            w = np.exp(s - s.max())
+            out[c, n] = w.sum() ** 2 / (w * w).sum()
+    return out.reshape(-1)

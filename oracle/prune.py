@@ -91,3 +91,14 @@ def depth_mask_seeded(T, n_drop, seed):
     mask = np.zeros(T, dtype=np.uint8)
     mask[order[:n_drop]] = 1
     return mask
+
+
+def mix_schedule(T, split_steps, window_mask, eta):
+    """Hybrid ODE-SDE schedule (ablation "Hybrid ODE-SDE"): split steps and the steps inside the
+    sliding window are SDE steps with diffusion coefficient eta, every other step is an ODE step.
+    -> (sigma float64 [T], ode_mask bool [T])."""
+    sde = np.zeros(T, dtype=bool)
+    for i in split_steps:
+        sde[i] = True
+    sde |= np.asarray(window_mask).astype(bool)
+    return np.where(sde, float(eta), 0.0), ~sde

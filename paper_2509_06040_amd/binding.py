@@ -28,7 +28,7 @@ EXPORTS = (
     "br_last_error", "br_tree_build", "br_tree_info", "br_tree_free", "br_model_create", "br_model_free",
     "br_workspace_bytes", "br_rollout", "br_logprob", "br_fuse_advantage", "br_prune", "br_reward_scratch_bytes",
     "br_leaf_reward", "br_grpo_objective", "br_velocity", "br_sde_scratch_bytes", "br_sde_step", "br_root_noise",
-    "br_noise_stream", "br_depth_mask_window", "br_depth_mask_seeded", "br_op_gemm", "br_op_attention",
+    "br_noise_stream", "br_depth_mask_window", "br_depth_mask_seeded", "br_mix_schedule", "br_fusion_ess", "br_op_gemm", "br_op_attention",
     "br_op_ln_modulate", "br_profile_enable", "br_profile_read",
 )
 
@@ -207,9 +207,13 @@ def leaf_reward(tree, z_nodes, kind, w, lam, latent, rewards, scratch):
                                  C.c_size_t(scratch.numel() * scratch.element_size()), _stream()))
 
 
-def grpo_objective(logp_new, logp_old_nodes, adv_nodes, edge_ids, n_edges, clip_eps, J):
+def grpo_objective(logp_new, logp_old_nodes, adv_nodes, edge_ids, n_edges, clip_eps, J, clipped=None):
     _check(load().br_grpo_objective(_p(logp_new), _p(logp_old_nodes), _p(adv_nodes), _p(edge_ids), C.c_int32(n_edges),
-                                    C.c_float(clip_eps), _p(J), _stream()))
+                                    C.c_float(clip_eps), _p(J), _p(clipped), _stream()))
+
+
+def fusion_ess(tree, logp_edges, beta, ess_nodes):
+    _check(load().br_fusion_ess(tree._h, _p(logp_edges), C.c_float(beta), _p(ess_nodes), _stream()))
 
 
 def velocity(model, z, t, cond_tokens, cond_index, v_out, workspace):
@@ -252,6 +256,19 @@ def depth_mask_seeded(T, n_drop, seed):
     _check(load().br_depth_mask_seeded(C.c_int32(T), C.c_int32(n_drop), C.c_uint64(seed),
                                        out.ctypes.data_as(C.c_void_p)))
     return out
+
+
+def mix_schedule(T, split_steps, window_mask, eta):
+    """-> (sigma [T] float32, ode_mask [T] uint8) of the hybrid ODE-SDE schedule."""
+    sp = np.ascontiguousarray(split_steps, dtype=np.int32)
+    wm = np.ascontiguousarray(window_mask, dtype=np.uint8)
+    if wm.shape != (T,):
+        raise ValueError("window_mask must have T entries")
+    sigma, ode = np.zeros(T, dtype=np.float32), np.zeros(T, dtype=np.uint8)
+    _check(load().br_mix_schedule(C.c_int32(T), sp.ctypes.data_as(C.c_void_p) if sp.size else C.c_void_p(0),
+                                  C.c_int32(sp.size), wm.ctypes.data_as(C.c_void_p), C.c_float(eta),
+                                  sigma.ctypes.data_as(C.c_void_p), ode.ctypes.data_as(C.c_void_p)))
+    return sigma, ode
 
 
 def op_gemm(dtype, epilogue, A, W, bias, out, mods=None, gate_off=0, cond=None, L=1, variant=-1):

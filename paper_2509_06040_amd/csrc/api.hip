@@ -274,14 +274,24 @@ extern "C" br_status br_leaf_reward(const br_tree* tree, const float* z_nodes, i
                             (float*)scratch, (hipStream_t)stream);
 }
 
+extern "C" br_status br_fusion_ess(const br_tree* tree, const float* logp_edges, float beta, float* ess_nodes,
+                                   void* stream) {
+  BR_REQUIRE(tree && logp_edges && ess_nodes, BR_EINVAL, "br_fusion_ess: NULL argument");
+  BR_REQUIRE(std::isfinite(beta), BR_EINVAL, "br_fusion_ess: beta must be finite");
+  TreeDev td;
+  br_status s;
+  if ((s = tree_device(tree, &td)) != BR_OK) return s;
+  return launch_fusion_ess(tree, td, logp_edges, beta, ess_nodes, (hipStream_t)stream);
+}
+
 extern "C" br_status br_grpo_objective(const float* logp_new, const float* logp_old_nodes, const float* adv_nodes,
                                        const int32_t* edge_ids, int32_t n_edges, float clip_eps, float* J,
-                                       void* stream) {
+                                       uint8_t* clipped, void* stream) {
   BR_REQUIRE(J != nullptr && n_edges >= 0, BR_EINVAL, "br_grpo_objective: J is NULL or n_edges < 0");
   BR_REQUIRE(n_edges == 0 || (logp_new && logp_old_nodes && adv_nodes && edge_ids), BR_EINVAL,
              "br_grpo_objective: NULL argument");
   BR_REQUIRE(std::isfinite(clip_eps) && clip_eps >= 0.f, BR_EINVAL, "br_grpo_objective: clip_eps must be >= 0");
-  return launch_grpo_objective(logp_new, logp_old_nodes, adv_nodes, edge_ids, n_edges, clip_eps, J,
+  return launch_grpo_objective(logp_new, logp_old_nodes, adv_nodes, edge_ids, n_edges, clip_eps, J, clipped,
                                (hipStream_t)stream);
 }
 

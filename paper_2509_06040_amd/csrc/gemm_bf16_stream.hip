@@ -45,6 +45,12 @@ template <int S>
 __shared__ __attribute__((aligned(1024))) char g_ring[STAGE];
 __shared__ __attribute__((aligned(1024))) char g_epi[NW * 4096];
 
+__device__ inline const char* uniform_ptr(const char* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const char*>(((unsigned long long)hi << 32) | lo);
+}
+
 // Maps the j-th tile of workgroup `wg` to (tile_m, tile_n); false when the list is exhausted.
 // Consecutive workgroup ids are spread over the 8 XCDs, so XCD x = wg % 8 gets a contiguous
 // range of tiles, shared by its workgroups in round-robin; inside the range tiles are walked in
@@ -104,6 +110,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   stream_tile(blockIdx.x, gridDim.x, 0, tiles_m, tiles_n, group_n, &tm, &tn);
   bool has_next = stream_tile(blockIdx.x, gridDim.x, 1, tiles_m, tiles_n, group_n, &tmn, &tnn);
 
+  // Per-lane byte offsets of an LDS-direct load from the first row of its 8-row block, for
+  // even and odd blocks (the swizzle of a row depends on the block only through its parity);
+  // the block's base address is uniform and is carried in scalar registers, so a load of a
+  // tile wholly inside the matrix costs no vector arithmetic at all.  Vector instructions
+  // and MFMAs do not overlap on this hardware: every one saved here is matrix time gained.
+  static_assert(IA % 2 == 0 && IW % 2 == 0, "block parity must follow the load index");
+  unsigned voff_a[2], voff_w[2];
+#pragma unroll
+  for (int par = 0; par < 2; ++par) {
+    const unsigned c = (lane & 7) ^ ((ld_row >> 1) | (4 * par));
+    voff_a[par] = (unsigned)ld_row * (unsigned)lda * 2 + c * 16;
+    voff_w[par] = (unsigned)ld_row * (unsigned)ldw * 2 + c * 16;
+  }
+
   // Stream element q of the current tile: stage q if q < nst, stage q - nst of the next tile
   // otherwise (the last stage again when there is no next tile: a fetch nobody reads).
   auto issue = [&](auto S, int q) {
@@ -112,19 +132,37 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
     const bool wrap = q >= nst && has_next;
     const unsigned kb = (unsigned)(wrap ? q - nst : min(q, nst - 1)) * (BK * 2);
     const int rm = (wrap ? tmn : tm) * BM, rn = (wrap ? tnn : tn) * BN;
-    const bf16* a_base = A;
-    const bf16* w_base = W;
+    if (rm + BM <= M && rn + BN <= N) {
+      // (the addresses are uniform; saying so keeps them in scalar registers in every instantiation)
+      const char* a_blk = uniform_ptr(reinterpret_cast<const char*>(A) + ((size_t)(rm + wv * IA * 8) * lda) * 2 + kb);
+      const char* w_blk = uniform_ptr(reinterpret_cast<const char*>(W) + ((size_t)(rn + wv * IW * 8) * ldw) * 2 + kb);
 #pragma unroll
-    for (int j = 0; j < IA; ++j) {
-      const unsigned src = src_off(rm, wv * IA + j, M, lda) + kb;
-      const unsigned dst = base + (wv * IA + j) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(a_base) : "memory", "m0");
-    }
+      for (int j = 0; j < IA; ++j) {
+        const unsigned dst = base + (wv * IA + j) * 1024;
+        const char* blk = a_blk + (size_t)j * 8 * lda * 2;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff_a[j & 1]), "s"(blk) : "memory", "m0");
+      }
 #pragma unroll
-    for (int j = 0; j < IW; ++j) {
-      const unsigned src = src_off(rn, wv * IW + j, N, ldw) + kb;
-      const unsigned dst = base + SA + (wv * IW + j) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(w_base) : "memory", "m0");
+      for (int j = 0; j < IW; ++j) {
+        const unsigned dst = base + SA + (wv * IW + j) * 1024;
+        const char* blk = w_blk + (size_t)j * 8 * ldw * 2;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff_w[j & 1]), "s"(blk) : "memory", "m0");
+      }
+    } else {  // ragged tile: rows past the end read the last row
+      const bf16* a_base = A;
+      const bf16* w_base = W;
+#pragma unroll
+      for (int j = 0; j < IA; ++j) {
+        const unsigned src = src_off(rm, wv * IA + j, M, lda) + kb;
+        const unsigned dst = base + (wv * IA + j) * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(a_base) : "memory", "m0");
+      }
+#pragma unroll
+      for (int j = 0; j < IW; ++j) {
+        const unsigned src = src_off(rn, wv * IW + j, N, ldw) + kb;
+        const unsigned dst = base + SA + (wv * IW + j) * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(src), "s"(w_base) : "memory", "m0");
+      }
     }
   };
 

@@ -39,6 +39,9 @@ br_status launch_fuse_advantage(const br_tree* t, const TreeDev& td, const float
 br_status launch_prune(const br_tree* t, const TreeDev& td, const float* r, int mode, int b, const DepthMask& dm,
                        int* kept, int* n_kept, hipStream_t st);
 br_status launch_grpo_objective(const float* logp_new, const float* logp_old_nodes, const float* adv_nodes,
-                                const int* edge_ids, int n, float clip_eps, float* J, hipStream_t st);
+                                const int* edge_ids, int n, float clip_eps, float* J, unsigned char* clipped,
+                                hipStream_t st);
+br_status launch_fusion_ess(const br_tree* t, const TreeDev& td, const float* logp, float beta, float* ess,
+                            hipStream_t st);
 
 }  // namespace br

@@ -1,6 +1,7 @@
 // Rollout-tree topology (Sec. 3.2 "Preliminaries"; Alg. 1, tree-building loop) and
 // the depth-pruning masks (Sec. 3.4), host side.
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <numeric>
 
@@ -165,6 +166,24 @@ extern "C" br_status br_depth_mask_window(int32_t T, int32_t last_split, int32_t
   int start = std::min(last_split + iter / every, stop - window);
   start = std::max(start, 0);
   for (int i = 0; i < T; ++i) mask_out[i] = (i >= start && i < start + window) ? 1 : 0;
+  return BR_OK;
+}
+
+extern "C" br_status br_mix_schedule(int32_t T, const int32_t* split_steps, int32_t n_splits,
+                                     const uint8_t* window_mask, float eta, float* sigma_out, uint8_t* ode_mask_out) {
+  BR_REQUIRE(sigma_out != nullptr && ode_mask_out != nullptr && window_mask != nullptr, BR_EINVAL,
+             "br_mix_schedule: NULL argument");
+  BR_REQUIRE(T >= 1 && n_splits >= 0 && (n_splits == 0 || split_steps != nullptr), BR_EINVAL,
+             "br_mix_schedule: arguments out of range");
+  BR_REQUIRE(std::isfinite(eta) && eta > 0.f, BR_EINVAL, "br_mix_schedule: eta must be positive");
+  for (int i = 0; i < n_splits; ++i)
+    BR_REQUIRE(split_steps[i] >= 0 && split_steps[i] < T, BR_EINVAL, "br_mix_schedule: split step outside [0, T)");
+  for (int i = 0; i < T; ++i) {
+    bool sde = window_mask[i] != 0;
+    for (int k = 0; k < n_splits; ++k) sde = sde || split_steps[k] == i;
+    sigma_out[i] = sde ? eta : 0.f;
+    ode_mask_out[i] = sde ? 0 : 1;
+  }
   return BR_OK;
 }
 

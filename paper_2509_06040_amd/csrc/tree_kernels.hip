@@ -193,6 +193,57 @@ __global__ __launch_bounds__(64) void fuse_advantage_kernel(TreeDev td, int T, i
   }
 }
 
+// Effective sample size of the fusion weights of every node (App., self-normalised importance
+// sampling view of Eq. 3): ESS(n) = (sum_l w_l)^2 / sum_l w_l^2 over the leaves under n, with
+// w_l = exp(beta S(l) - max).  One wavefront per tree, same leaf path sums as the fusion.
+__global__ __launch_bounds__(64) void fusion_ess_kernel(TreeDev td, int T, int n_nodes, int w,
+                                                        const float* __restrict__ logp, double beta,
+                                                        float* __restrict__ ess_out) {
+  extern __shared__ double S[];
+  const int c = blockIdx.x, lane = threadIdx.x;
+  const float* lp = logp + (size_t)c * n_nodes;
+  const int leaf0 = td.off[T];
+  for (int l = lane; l < w; l += 64) {
+    double s = 0.0;
+    for (int n = leaf0 + l; td.parent[n] >= 0; n = td.parent[n]) s += (double)lp[n];
+    S[l] = s;
+  }
+  __syncthreads();
+  for (int d = 0; d <= T; ++d) {
+    const int lo_n = td.off[d], wd = td.off[d + 1] - lo_n, span = w / wd;
+    if (span >= 32) {
+      for (int j = 0; j < wd; ++j) {
+        const int lo = j * span, hi = lo + span;
+        double m = -INFINITY;
+        for (int l = lo + lane; l < hi; l += 64) m = fmax(m, beta * S[l]);
+        m = wmax_d(m);
+        double s1 = 0.0, s2 = 0.0;
+        for (int l = lo + lane; l < hi; l += 64) {
+          const double e = exp(beta * S[l] - m);
+          s1 += e;
+          s2 += e * e;
+        }
+        s1 = wsum_d(s1);
+        s2 = wsum_d(s2);
+        if (lane == 0) ess_out[(size_t)c * n_nodes + lo_n + j] = (float)(s1 * s1 / s2);
+      }
+    } else {
+      for (int j = lane; j < wd; j += 64) {
+        const int lo = j * span, hi = lo + span;
+        double m = -INFINITY;
+        for (int l = lo; l < hi; ++l) m = fmax(m, beta * S[l]);
+        double s1 = 0.0, s2 = 0.0;
+        for (int l = lo; l < hi; ++l) {
+          const double e = exp(beta * S[l] - m);
+          s1 += e;
+          s2 += e * e;
+        }
+        ess_out[(size_t)c * n_nodes + lo_n + j] = (float)(s1 * s1 / s2);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ pruning
 __device__ inline bool dm_get(const DepthMask& dm, int i) { return (dm.bits[i >> 5] >> (i & 31)) & 1u; }
 
@@ -291,7 +342,8 @@ __global__ __launch_bounds__(256) void grpo_objective_kernel(const float* __rest
                                                              const float* __restrict__ logp_old,
                                                              const float* __restrict__ adv,
                                                              const int* __restrict__ ids, int n, double clip_eps,
-                                                             float* __restrict__ J) {
+                                                             float* __restrict__ J,
+                                                             unsigned char* __restrict__ clipped) {
   __shared__ double red[4];
   double acc = 0.0;
   for (int e = threadIdx.x; e < n; e += 256) {
@@ -299,6 +351,7 @@ __global__ __launch_bounds__(256) void grpo_objective_kernel(const float* __rest
     const double rho = exp((double)logp_new[e] - (double)logp_old[g]), a = adv[g];
     const double cl = fmin(fmax(rho, 1.0 - clip_eps), 1.0 + clip_eps);
     acc += fmin(rho * a, cl * a);
+    if (clipped) clipped[e] = cl * a < rho * a ? 1 : 0;  // the clipped term is the one taken
   }
   acc = wsum_d(acc);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
@@ -350,6 +403,15 @@ br_status launch_fuse_advantage(const br_tree* t, const TreeDev& td, const float
   return BR_OK;
 }
 
+br_status launch_fusion_ess(const br_tree* t, const TreeDev& td, const float* logp, float beta, float* ess,
+                            hipStream_t st) {
+  BR_REQUIRE(t->n_leaves <= 4096, BR_ESHAPE, "ess: more than 4096 leaves per tree are not supported");
+  hipLaunchKernelGGL(fusion_ess_kernel, dim3(t->n_tree), dim3(64), (size_t)t->n_leaves * sizeof(double), st, td, t->T,
+                     t->n_nodes, t->n_leaves, logp, (double)beta, ess);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
+}
+
 br_status launch_prune(const br_tree* t, const TreeDev& td, const float* r, int mode, int b, const DepthMask& dm,
                        int* kept, int* n_kept, hipStream_t st) {
   BR_REQUIRE(t->n_leaves <= 8191, BR_ESHAPE, "prune: more than 8191 leaves per tree are not supported");
@@ -363,9 +425,10 @@ br_status launch_prune(const br_tree* t, const TreeDev& td, const float* r, int 
 }
 
 br_status launch_grpo_objective(const float* logp_new, const float* logp_old_nodes, const float* adv_nodes,
-                                const int* edge_ids, int n, float clip_eps, float* J, hipStream_t st) {
+                                const int* edge_ids, int n, float clip_eps, float* J, unsigned char* clipped,
+                                hipStream_t st) {
   hipLaunchKernelGGL(grpo_objective_kernel, dim3(1), dim3(256), 0, st, logp_new, logp_old_nodes, adv_nodes, edge_ids, n,
-                     (double)clip_eps, J);
+                     (double)clip_eps, J, clipped);
   BR_LAUNCH_CHECK();
   return BR_OK;
 }

@@ -132,6 +132,43 @@ def test_ode_steps_in_the_rollout(lib):
         assert (lp[n] == 0.0) == (t.depth[n] - 1 in (0, 3, 7))
 
 
+def test_hybrid_ode_sde_schedule_end_to_end(lib):
+    """Hybrid ODE-SDE ablation: split steps and a sliding window stay stochastic, the other steps are
+    deterministic, carry no log-prob and are left out of the update."""
+    wl = synth.WORKLOADS["tiny"]
+    T, splits, C = wl["T"], wl["splits"], 2
+    win = br.depth_mask_window(T, splits[-1], 2, 0, 30, T)
+    sigma, ode = br.mix_schedule(T, splits, win, synth.ETA)
+    assert 0 < ode.sum() < T
+    r = _run_rollout(wl, C, 77, [0, 1], ode_steps=tuple(np.nonzero(ode)[0]))
+    assert np.array_equal(r["sched"]["sigma"], sigma)
+    t, cfg, W, cond, sched, D = r["t"], r["cfg"], r["W"], r["cond"], r["sched"], r["D"]
+    o = tree.tree_build(T, splits, wl["K"])
+    vel = lambda zz, tt, ci: dit.forward(cfg, W, zz, tt, cond, ci)
+    zr, lpr, _ = rollout.tree_rollout(o, vel, sched, 77, [0, 1], D, C)
+    z, lp = host(r["z"]), host(r["logp"])
+    assert np.abs(z - zr).max() < 2e-4
+    for n in range(C * t.n_nodes):
+        step = t.depth[n % t.n_nodes] - 1
+        if step < 0 or ode[step]:
+            assert lp[n] == 0.0 and lpr[n] == 0.0
+        else:
+            assert abs(lp[n] - lpr[n]) <= 1e-3 * abs(lpr[n])
+    # the ODE mask as depth mask keeps exactly the edges of stochastic steps
+    rew = dev(np.arange(C * t.n_leaves, dtype=np.float32))
+    kept = torch.empty(C * t.n_edges, dtype=torch.int32, device=DEV)
+    nk = torch.zeros(1, dtype=torch.int32, device=DEV)
+    br.prune(t, rew, br.PRUNE_NONE, 0, ode, kept, nk)
+    ids = host(kept)[:int(host(nk)[0])]
+    assert np.array_equal(ids, prune.kept_edges(o, host(rew), C, 0, 0, ode))
+    assert all(not ode[t.depth[g % t.n_nodes] - 1] for g in ids) and len(ids) == sum(
+        C * t.width[i + 1] for i in range(T) if not ode[i])
+    out = torch.empty(len(ids), device=DEV)
+    br.logprob(t, r["model"], sched, cond_dev(cfg, cond), r["z"], ids, out, r["ws"])
+    ref = rollout.edge_logprob(o, vel, sched, z.astype(np.float64), ids, C)
+    assert np.all(np.abs(host(out) - ref) <= 1e-3 * np.abs(ref))
+
+
 def test_rollout_rejects_bad_arguments(lib):
     wl = synth.WORKLOADS["tiny"]
     r = _run_rollout(wl, 1, 3, [0])

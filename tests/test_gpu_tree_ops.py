@@ -108,9 +108,28 @@ def test_grpo_objective_matches_oracle(lib):
     adv = rng.standard_normal(n_nodes).astype(np.float32) * 2
     ln = (lo[ids] + rng.standard_normal(n).astype(np.float32) * 1e-2).astype(np.float32)
     J = torch.empty(1, device=DEV)
+    clipped = torch.empty(n, dtype=torch.uint8, device=DEV)
     for eps in (1e-4, 0.2):
-        br.grpo_objective(dev(ln), dev(lo), dev(adv), dev(ids), n, eps, J)
-        ref, _ = objective.grpo_objective(ln, lo[ids], adv[ids], eps)
+        br.grpo_objective(dev(ln), dev(lo), dev(adv), dev(ids), n, eps, J, clipped)
+        ref, ref_clipped = objective.grpo_objective(ln, lo[ids], adv[ids], eps)
+        assert abs(float(host(J)[0]) - ref) < 1e-6
+        assert np.array_equal(host(clipped).astype(bool), ref_clipped)
+        assert (0 < ref_clipped.sum() < n) == (eps == 1e-4)      # |log rho| ~ 1e-2: only the tight range clips
+        br.grpo_objective(dev(ln), dev(lo), dev(adv), dev(ids), n, eps, J)          # the mask is optional
         assert abs(float(host(J)[0]) - ref) < 1e-6
     br.grpo_objective(dev(ln), dev(lo), dev(adv), dev(ids), 0, 0.2, J)
     assert float(host(J)[0]) == 0.0
+
+
+@pytest.mark.parametrize("T,splits,K,C", [(8, (2, 4, 6), 2, 1), (20, (4, 8, 12, 16), 2, 4), (20, (0, 3, 6, 9), 3, 3),
+                                          (16, (3, 6, 9, 12), 4, 2), (6, (), 2, 2)])
+def test_fusion_ess_matches_oracle(lib, T, splits, K, C):
+    t, o = br.Tree(T, splits, K, n_tree=C), tree.tree_build(T, splits, K)
+    rng = np.random.default_rng(T + K)
+    n = C * t.n_nodes
+    logp = (rng.standard_normal(n) * 0.7).astype(np.float32)
+    ess = torch.full((n,), -1.0, device=DEV)
+    for beta in (1.0, 0.0, 3.5):
+        br.fusion_ess(t, dev(logp), beta, ess)
+        ref = fusion.ess(o, logp, beta, C)
+        assert np.all(np.abs(host(ess) - ref) <= 1e-5 * ref), beta

@@ -68,6 +68,18 @@ def test_depth_masks_match_the_oracle():
         br.depth_mask_seeded(5, 6, 1)
 
 
+def test_hybrid_schedule_matches_the_oracle():
+    for T, splits, it in ((20, (4, 8, 12, 16), 0), (20, (0, 3, 6, 9), 95), (16, (3, 6, 9, 12), 3000), (5, (), 0)):
+        win = br.depth_mask_window(T, splits[-1] if splits else 0, 4, it, 30, T)
+        sigma, ode = br.mix_schedule(T, splits, win, 0.3)
+        ref_sigma, ref_ode = prune.mix_schedule(T, splits, win, 0.3)
+        assert np.array_equal(sigma, ref_sigma.astype(np.float32)) and np.array_equal(ode.astype(bool), ref_ode)
+    with pytest.raises(br.BranchRolloutError):
+        br.mix_schedule(5, (5,), np.zeros(5, np.uint8), 0.3)          # split step outside [0, T)
+    with pytest.raises(br.BranchRolloutError):
+        br.mix_schedule(5, (1,), np.zeros(5, np.uint8), 0.0)          # eta must be positive
+
+
 def test_model_create_validates_shapes():
     lib = br.load()
     cfg = br.ModelCfg(2, 64, 4, 4, 4, 1, 8, 8, 1, 2, 2, 8, 64, br.F32)

@@ -142,3 +142,33 @@ def test_grpo_objective_hand_values():
     J, clipped = objective.grpo_objective([-0.5, -0.5], [0.0, 0.0], [2.0, -2.0], 0.2)
     assert np.isclose(J, (np.exp(-0.5) * 2.0 + 0.8 * -2.0) / 2)
     assert list(clipped) == [False, True]
+
+
+def test_ess_of_fusion_weights():
+    # appendix (self-normalised importance sampling): ESS = (sum w)^2 / sum w^2
+    t = tree.tree_build(4, (0, 2), 2)                      # 4 leaves, widths 1,2,2,4,4
+    n, off = t["n_nodes"], t["off"]
+    # uniform weights: ESS = number of leaves under the node
+    e = fusion.ess(t, np.zeros(n), 1.0, 1)
+    assert np.allclose(e, np.array(t["leaf_hi"]) - np.array(t["leaf_lo"]))
+    # two leaves under a depth-2 node with weights 3:1 -> 1 / (0.75^2 + 0.25^2) = 1.6
+    lp = np.zeros(n)
+    lp[off[3] + 0] = np.log(3.0)                           # edge into the first depth-3 node (split at step 2)
+    e = fusion.ess(t, lp, 1.0, 1)
+    assert np.isclose(e[off[2] + 0], 1.6) and np.isclose(e[off[2] + 1], 2.0)
+    assert np.isclose(e[off[3] + 0], 1.0) and np.isclose(e[off[4] + 2], 1.0)
+    # root: weights 3,1,1,1 -> 36 / 12 = 3; with beta = 0 the weights are uniform again
+    assert np.isclose(e[0], 3.0)
+    assert np.isclose(fusion.ess(t, lp, 0.0, 1)[0], 4.0)
+    # one dominating leaf -> ESS -> 1; shifting all log-probs of a depth changes nothing
+    lp2 = np.zeros(n)
+    lp2[off[4] + 1] = 50.0
+    assert np.isclose(fusion.ess(t, lp2, 1.0, 1)[0], 1.0)
+    lp3 = lp.copy()
+    lp3[off[1]:off[2]] += 7.5
+    assert np.allclose(fusion.ess(t, lp3, 1.0, 1), e)
+    # consistency with the fused reward: with rewards = leaf weights' indicator the weights are recovered
+    rng = np.random.default_rng(5)
+    lp4 = rng.standard_normal(n)
+    w = np.array([fusion.fuse_rewards(t, np.eye(4)[l], lp4, 1.3, 1)[0] for l in range(4)])   # root weights of each leaf
+    assert np.isclose(fusion.ess(t, lp4, 1.3, 1)[0], w.sum() ** 2 / (w * w).sum())

@@ -74,3 +74,22 @@ def test_seeded_depth_subset():
     assert np.array_equal(m, prune.depth_mask_seeded(20, 4, 42))
     assert not np.array_equal(m, prune.depth_mask_seeded(20, 4, 43))
     assert prune.depth_mask_seeded(20, 0, 42).sum() == 0 and prune.depth_mask_seeded(5, 5, 1).all()
+
+
+def test_hybrid_ode_sde_schedule():
+    # ablation "Hybrid ODE-SDE": split steps stay SDE, the window adds SDE steps, the rest are ODE steps
+    win = prune.depth_mask_window(20, 16, 4, 0, 30, 20)          # steps 16..19
+    sigma, ode = prune.mix_schedule(20, (4, 8, 12, 16), win, 0.3)
+    sde_steps = sorted(set((4, 8, 12, 16)) | {16, 17, 18, 19})
+    assert list(np.nonzero(sigma)[0]) == sde_steps and np.all(sigma[sde_steps] == 0.3)
+    assert list(np.nonzero(ode)[0]) == [i for i in range(20) if i not in sde_steps]
+    # an empty window leaves only the split steps stochastic; a full window gives the plain SDE sampler
+    sigma, ode = prune.mix_schedule(6, (1, 3), np.zeros(6, np.uint8), 0.7)
+    assert list(sigma) == [0.0, 0.7, 0.0, 0.7, 0.0, 0.0] and list(ode) == [True, False, True, False, True, True]
+    sigma, ode = prune.mix_schedule(6, (), np.ones(6, np.uint8), 0.7)
+    assert np.all(sigma == 0.7) and not ode.any()
+    # edges of ODE steps leave the update when the ODE mask is used as depth mask
+    t = tree.tree_build(6, (1, 3), 2)
+    _, ode = prune.mix_schedule(6, (1, 3), np.zeros(6, np.uint8), 0.7)
+    kept = prune.kept_edges(t, np.arange(t["n_leaves"], dtype=float), 1, 0, 0, ode.astype(np.uint8))
+    assert sorted(set(t["depth"][k] - 1 for k in kept)) == [1, 3]
