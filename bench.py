@@ -200,6 +200,42 @@ def main():
         tot_ms = sum(v["total_ms"] for v in mf)
         roofline["network_mfma_frac"] = round(tot_flop / tot_ms / PEAK_BF16_TFLOPS, 4) if tot_ms else None
 
+    # ---- the memory-bound and latency-bound calls alone, after the timed region: the fused SDE step on the
+    # largest plain frontier and on the last split step, the leaf rewards, fusion + advantages, pruning
+    def timed_us(fn, reps=20):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
+
+    small_calls = {}
+    sde_scratch = torch.empty(max(256, br.sde_scratch_bytes(tree, D)), dtype=torch.uint8, device=dev)
+    steps = [T - 1] + ([max(wl["splits"])] if wl["K"] > 1 and len(wl["splits"]) else [])
+    for name, i in zip(("sde_step_largest_frontier", "sde_step_last_split"), steps):
+        parents, children = C * int(tree.width[i]), C * int(tree.width[i + 1])
+        vpar = torch.randn((parents, D), device=dev)
+        us = timed_us(lambda: br.sde_step(tree, sched, 5, i, D, vpar, z, logp, sde_scratch))
+        nbytes = (2 * parents + children) * 4.0 * D + 4.0 * children          # read z, v per parent; write children
+        small_calls[name] = dict(step=int(i), parents=parents, children=children, us=round(us, 2),
+                                 algorithmic_bytes=int(nbytes), achieved_GBps=round(nbytes / us / 1e3, 1),
+                                 frac_of_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+        del vpar
+    us = timed_us(lambda: br.leaf_reward(tree, z, kind, w_rew, 0.0, latent, rew, rs))
+    nbytes = 4.0 * D * n_leaves + 4.0 * D
+    small_calls["leaf_reward"] = dict(leaves=n_leaves, us=round(us, 2), algorithmic_bytes=int(nbytes),
+                                      achieved_GBps=round(nbytes / us / 1e3, 1),
+                                      frac_of_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+    small_calls["fuse_advantage"] = dict(us=round(timed_us(
+        lambda: br.fuse_advantage(tree, rew, logp, 1.0, 1e-8, 0, synth.ADV_CLIP, rbar, adv)), 2), bound="launch latency")
+    small_calls["prune"] = dict(us=round(timed_us(
+        lambda: br.prune(tree, rew, br.PRUNE_EXTREME, b_extreme, depth_mask, kept, n_kept)), 2), bound="launch latency")
+    step(synth.SAMPLER_SEED + 100 + args.steps - 1, False)     # leave the arena as the last timed step left it
+
     # ---- model FLOPs of a step (2MNK per GEMM, 4 L^2 H per attention block) / wall time
     fwd_flop = NB * (24.0 * L * H * H + 4.0 * L * L * H) + 4.0 * sz["n_img"] * sz["patch_dim"] * H
     n_eval_roll = C * int(sum(tree.width[:T]))
@@ -278,7 +314,7 @@ def main():
                phase_ms={k: round(v, 3) for k, v in phase_ms.items()},
                mfma_util_step=round(step_mfma_util, 4), mfma_util_rollout=round(rollout_mfma_util, 4),
                network_evals=dict(rollout=n_eval_roll, logprob=n_eval_lp, flop_per_eval=fwd_flop),
-               roofline=roofline, kernels=kernels, flat_rollout=flat, cpu_baseline=cpu)
+               roofline=roofline, kernels=kernels, small_calls=small_calls, flat_rollout=flat, cpu_baseline=cpu)
     print(json.dumps(out))
 
 
