@@ -8,6 +8,8 @@
 // the dispatch; the persistent kernel for large problems is in gemm_bf16_stream.hip.
 #include <type_traits>
 
+#include <cmath>
+
 #include "common.h"
 #include "dit.h"
 #include "gemm_epilogue.h"
@@ -222,11 +224,19 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
                               int variant, hipStream_t st) {
   int tile, group_n = 0;
   if (variant < 0) {
-    // measured on MI355X: the persistent 256x256 kernel wins once there are enough tiles to
-    // fill the 256 compute units or the output is wide; otherwise 256x128 tiles
+    // Measured on MI355X (256 compute units).  With r = (256x256 tiles) / (compute units):
+    // up to half a round of tiles, 256x128 tiles put twice as many units to work; up to one
+    // round the persistent 256x256 kernel is best; beyond that it stays best unless the last
+    // round would be mostly empty (r = 1.08 costs two rounds), where 128x128 tiles win.
     const long long t256 = (long long)cdiv(M, 256) * cdiv(N, 256);
-    const bool big = t256 >= 200 || N >= 3072;
-    tile = big ? (gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2) ? 7 : 4) : 6;
+    const double r = (double)t256 / 256.0;
+    const bool stream_ok = gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2);
+    if (r <= 0.5)
+      tile = 6;
+    else if (r > 1.0 && std::ceil(r) / r > 1.4)
+      tile = 5;
+    else
+      tile = stream_ok ? 7 : 4;
   } else {
     tile = variant & 15;
     group_n = (variant >> 4) & 255;
