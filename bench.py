@@ -87,7 +87,7 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (conditions are independent trees and would shard "
+        sys.exit("bench.py: the measurement covers one GPU only (conditions are independent trees and would shard "
                  "across GPUs without collectives); run with --gpus 1")
 
     import torch
@@ -213,18 +213,56 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e3 / reps
 
+    def sde_kernel_us(fn, reps=20):
+        """Average duration of the fused step kernel alone (HIP events on the launch stream around that kernel;
+        the call also launches the small kernel that sums the per-block log-prob partials)."""
+        fn()
+        torch.cuda.synchronize()
+        br.profile_enable(True)
+        br.profile_read()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        work, ms, cnt = br.profile_read()[200]
+        br.profile_enable(False)
+        return ms * 1e3 / cnt
+
     small_calls = {}
     sde_scratch = torch.empty(max(256, br.sde_scratch_bytes(tree, D)), dtype=torch.uint8, device=dev)
     steps = [T - 1] + ([max(wl["splits"])] if wl["K"] > 1 and len(wl["splits"]) else [])
     for name, i in zip(("sde_step_largest_frontier", "sde_step_last_split"), steps):
         parents, children = C * int(tree.width[i]), C * int(tree.width[i + 1])
         vpar = torch.randn((parents, D), device=dev)
-        us = timed_us(lambda: br.sde_step(tree, sched, 5, i, D, vpar, z, logp, sde_scratch))
+        call = lambda: br.sde_step(tree, sched, 5, i, D, vpar, z, logp, sde_scratch)
+        us, kus = timed_us(call), sde_kernel_us(call)
         nbytes = (2 * parents + children) * 4.0 * D + 4.0 * children          # read z, v per parent; write children
-        small_calls[name] = dict(step=int(i), parents=parents, children=children, us=round(us, 2),
-                                 algorithmic_bytes=int(nbytes), achieved_GBps=round(nbytes / us / 1e3, 1),
-                                 frac_of_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+        small_calls[name] = dict(step=int(i), parents=parents, children=children, call_us=round(us, 2),
+                                 kernel_us=round(kus, 2), algorithmic_bytes=int(nbytes),
+                                 achieved_GBps=round(nbytes / kus / 1e3, 1),
+                                 frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4))
         del vpar
+    # the same kernel on the largest frontier of the other workload shapes (their networks are not run here)
+    for other in ("image_large", "video"):
+        if other == args.workload:
+            continue
+        ow = synth.WORKLOADS[other]
+        oD = synth.model_sizes(ow["model"])["D"]
+        otree = br.Tree(ow["T"], ow["splits"], ow["K"], n_tree=ow["n_cond"])
+        oz = torch.empty((ow["n_cond"] * otree.n_nodes, oD), device=dev).normal_()
+        olp = torch.empty(ow["n_cond"] * otree.n_nodes, device=dev)
+        osched = synth.schedule(ow["T"], ow["kappa"], logp_mean=True)
+        oscr = torch.empty(max(256, br.sde_scratch_bytes(otree, oD)), dtype=torch.uint8, device=dev)
+        i = ow["T"] - 1
+        parents = ow["n_cond"] * int(otree.width[i])
+        vpar = torch.randn((parents, oD), device=dev)
+        call = lambda: br.sde_step(otree, osched, 5, i, oD, vpar, oz, olp, oscr)
+        us, kus = timed_us(call), sde_kernel_us(call)
+        nbytes = 3 * parents * 4.0 * oD + 4.0 * parents
+        small_calls["sde_step_largest_frontier[%s]" % other] = dict(
+            step=int(i), parents=parents, children=parents, D=int(oD), call_us=round(us, 2), kernel_us=round(kus, 2),
+            algorithmic_bytes=int(nbytes), achieved_GBps=round(nbytes / kus / 1e3, 1),
+            frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4))
+        del oz, olp, oscr, vpar, otree
     us = timed_us(lambda: br.leaf_reward(tree, z, kind, w_rew, 0.0, latent, rew, rs))
     nbytes = 4.0 * D * n_leaves + 4.0 * D
     small_calls["leaf_reward"] = dict(leaves=n_leaves, us=round(us, 2), algorithmic_bytes=int(nbytes),
