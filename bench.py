@@ -66,12 +66,15 @@ def measured_traffic(label):
     return round(t["bytes_per_launch"]) if h.hexdigest() == t["sha1"] else None
 
 
+HBM_KERNELS = {200: "sde_step", 201: "logp_eval", 300: "ln_modulate"}
+
+
 def kernel_label(kid):
+    if kid in HBM_KERNELS:
+        return HBM_KERNELS[kid]
     if kid < 100:
         return "gemm_bf16[%s,%s]" % (GEMM_NAMES[kid // 8], TILE_NAMES[kid % 8])
-    if kid < 200:
-        return "attn_bf16[d%d]" % (kid - 100)
-    return {200: "sde_step", 201: "logp_eval", 300: "ln_modulate"}[kid]
+    return "attn_bf16[d%d]" % (kid - 100)
 
 
 def main():
@@ -79,7 +82,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="image", choices=["image", "tiny"])
+    ap.add_argument("--workload", default="image", choices=["image", "tiny", "image_large", "video"],
+                    help="image is the workload of the headline metric; the others are extra shapes")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time single launches in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
@@ -115,8 +119,9 @@ def main():
     n_leaves = C * tree.n_leaves
     n = C * tree.n_nodes
     groups = list(range(C))
-    w_rew = torch.from_numpy(synth.reward_vector(D, 7)).to(dev)
-    kind = {"linear": br.REWARD_LINEAR, "tanh": br.REWARD_TANH}[wl["reward"]]
+    kind = {"linear": br.REWARD_LINEAR, "tanh": br.REWARD_TANH, "video": br.REWARD_VIDEO}[wl["reward"]]
+    lam = 0.1 if kind == br.REWARD_VIDEO else 0.0
+    w_rew = torch.from_numpy(synth.reward_vector(latent[0] * latent[1] if kind == br.REWARD_VIDEO else D, 7)).to(dev)
     depth_mask = br.depth_mask_seeded(T, min(4, T), synth.DATA_SEED)
     b_extreme = max(1, tree.n_leaves // 4)
 
@@ -140,7 +145,7 @@ def main():
         br.rollout(tree, model, sched, seed, groups, cond, z, logp, None, ws)
         if timed:
             ev[1].record()
-        br.leaf_reward(tree, z, kind, w_rew, 0.0, latent, rew, rs)
+        br.leaf_reward(tree, z, kind, w_rew, lam, latent, rew, rs)
         br.fuse_advantage(tree, rew, logp, 1.0, 1e-8, 0, synth.ADV_CLIP, rbar, adv)
         br.prune(tree, rew, br.PRUNE_EXTREME, b_extreme, depth_mask, kept, n_kept)
         nk = int(n_kept.cpu()[0])                       # the only host round trip of a step
@@ -183,7 +188,7 @@ def main():
     # ---- roofline of the dominant kernel (largest total time among the instrumented ones)
     kernels = {}
     for kid, (work, ms, cnt) in prof.items():
-        mfma = kid < 200
+        mfma = kid not in HBM_KERNELS
         ach = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
         peak = PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS
         kernels[kernel_label(kid)] = dict(bound="mfma" if mfma else "hbm", launches=int(cnt), total_ms=round(ms, 3),
@@ -263,7 +268,7 @@ def main():
             algorithmic_bytes=int(nbytes), achieved_GBps=round(nbytes / kus / 1e3, 1),
             frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4))
         del oz, olp, oscr, vpar, otree
-    us = timed_us(lambda: br.leaf_reward(tree, z, kind, w_rew, 0.0, latent, rew, rs))
+    us = timed_us(lambda: br.leaf_reward(tree, z, kind, w_rew, lam, latent, rew, rs))
     nbytes = 4.0 * D * n_leaves + 4.0 * D
     small_calls["leaf_reward"] = dict(leaves=n_leaves, us=round(us, 2), algorithmic_bytes=int(nbytes),
                                       achieved_GBps=round(nbytes / us / 1e3, 1),
