@@ -121,7 +121,7 @@ __device__ inline double rbar_lane(const FuseCtx& cx, int lo, int hi) {
 }
 // The same by the whole wavefront (result in every lane).
 __device__ inline double rbar_wave(const FuseCtx& cx, int lo, int hi) {
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
   double m = -INFINITY;
   for (int l = lo + lane; l < hi; l += 64) m = fmax(m, cx.beta * cx.S[l]);
   m = wmax_d(m);
@@ -189,6 +189,64 @@ __global__ __launch_bounds__(64) void fuse_advantage_kernel(TreeDev td, int T, i
         const double sd = dof > 0 ? sqrt(acc / (double)dof) : 0.0;
         inv = (dof > 0 && sd + eps > 0.0) ? 1.0 / (sd + eps) : 0.0;
       }
+    }
+  }
+}
+
+// The same for trees whose leaf path sums and fused rewards fit in LDS (every tree of the
+// paper's presets does): one workgroup of four wavefronts per tree.  Every node's fused reward is
+// computed once -- nodes with 64 or more leaves by a whole wavefront, the others by one lane each,
+// all in parallel -- and kept in LDS; the depths are then normalised from there, one wavefront
+// per depth.  Summation orders are fixed, so the result does not depend on timing.
+__global__ __launch_bounds__(256) void fuse_advantage_lds_kernel(TreeDev td, int T, int n_nodes, int w,
+                                                                 const float* __restrict__ rewards,
+                                                                 const float* __restrict__ logp, double beta,
+                                                                 double eps, int ddof, double a_max,
+                                                                 float* __restrict__ rbar_out,
+                                                                 float* __restrict__ adv_out) {
+  extern __shared__ double sh[];
+  double* S = sh;        // [w] leaf path sums
+  double* RB = sh + w;   // [n_nodes] fused rewards
+  const int c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const float* lp = logp + (size_t)c * n_nodes;
+  const int leaf0 = td.off[T];
+  for (int l = tid; l < w; l += 256) {
+    double s = 0.0;
+    for (int n = leaf0 + l; td.parent[n] >= 0; n = td.parent[n]) s += (double)lp[n];
+    S[l] = s;
+  }
+  __syncthreads();
+  FuseCtx cx{S, rewards + (size_t)c * w, beta};
+  // nodes with many leaves: depth by depth, one wavefront per node
+  int first_small = 0;  // first node (level order) with fewer than 64 leaves
+  for (int d = 0; d <= T; ++d) {
+    const int lo_n = td.off[d], wd = td.off[d + 1] - lo_n, span = w / wd;
+    if (span < 64) break;
+    for (int j = wv; j < wd; j += 4) {
+      const double rb = rbar_wave(cx, j * span, (j + 1) * span);
+      if (lane == 0) RB[lo_n + j] = rb;
+    }
+    first_small = lo_n + wd;
+  }
+  for (int n = first_small + tid; n < n_nodes; n += 256) RB[n] = rbar_lane(cx, td.leaf_lo[n], td.leaf_hi[n]);
+  __syncthreads();
+  for (int d = wv; d <= T; d += 4) {
+    const int lo_n = td.off[d], wd = td.off[d + 1] - lo_n;
+    double acc = 0.0;
+    for (int j = lane; j < wd; j += 64) acc += RB[lo_n + j];
+    const double mean = wsum_d(acc) / (double)wd;
+    acc = 0.0;
+    for (int j = lane; j < wd; j += 64) acc += (RB[lo_n + j] - mean) * (RB[lo_n + j] - mean);
+    acc = wsum_d(acc);
+    const int dof = wd - ddof;
+    const double sd = dof > 0 ? sqrt(acc / (double)dof) : 0.0;
+    const double inv = (dof > 0 && sd + eps > 0.0) ? 1.0 / (sd + eps) : 0.0;
+    for (int j = lane; j < wd; j += 64) {
+      const double rb = RB[lo_n + j];
+      double a = (rb - mean) * inv;
+      if (a_max > 0.0) a = fmin(fmax(a, -a_max), a_max);
+      rbar_out[(size_t)c * n_nodes + lo_n + j] = (float)rb;
+      adv_out[(size_t)c * n_nodes + lo_n + j] = (float)a;
     }
   }
 }
@@ -397,6 +455,13 @@ br_status launch_leaf_reward(const br_tree* t, const float* z, int kind, const f
 br_status launch_fuse_advantage(const br_tree* t, const TreeDev& td, const float* r, const float* logp, float beta,
                                 float eps, int ddof, float a_max, float* rbar, float* adv, hipStream_t st) {
   BR_REQUIRE(t->n_leaves <= 4096, BR_ESHAPE, "fuse: more than 4096 leaves per tree are not supported");
+  const size_t cached = ((size_t)t->n_leaves + (size_t)t->n_nodes) * sizeof(double);
+  if (cached <= 48 * 1024) {
+    hipLaunchKernelGGL(fuse_advantage_lds_kernel, dim3(t->n_tree), dim3(256), cached, st, td, t->T, t->n_nodes,
+                       t->n_leaves, r, logp, (double)beta, (double)eps, ddof, (double)a_max, rbar, adv);
+    BR_LAUNCH_CHECK();
+    return BR_OK;
+  }
   hipLaunchKernelGGL(fuse_advantage_kernel, dim3(t->n_tree), dim3(64), (size_t)t->n_leaves * sizeof(double), st, td,
                      t->T, t->n_nodes, t->n_leaves, r, logp, (double)beta, (double)eps, ddof, (double)a_max, rbar, adv);
   BR_LAUNCH_CHECK();

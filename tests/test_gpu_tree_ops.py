@@ -41,7 +41,8 @@ def test_fusion_hand_worked_trees(lib, name):
 @pytest.mark.parametrize("T,splits,K,C,lp_scale", [(8, (2, 4, 6), 2, 1, 1.0), (20, (4, 8, 12, 16), 2, 4, 0.05),
                                                    (20, (0, 3, 6, 9), 3, 2, 2.0), (16, (3, 6, 9, 12), 4, 2, 300.0),
                                                    (10, (0, 1, 2, 3, 4, 5, 6), 2, 2, 1.0), (6, (), 2, 3, 1.0),
-                                                   (5, (1, 3), 1, 5, 1.0)])
+                                                   (5, (1, 3), 1, 5, 1.0),
+                                                   (100, (0, 1, 2, 3, 4, 5), 2, 1, 0.3)])      # 6143 nodes: not LDS-cached
 def test_fusion_and_advantages_match_oracle(lib, T, splits, K, C, lp_scale):
     t = br.Tree(T, splits, K, n_tree=C)
     o = tree.tree_build(T, splits, K)
