@@ -176,7 +176,9 @@ br_status br_rollout(const br_tree* tree, const br_model* model, const br_sched*
  * Eq. 5): for edge e with child c = edge_ids[e], parent p, step i = depth(c)-1:
  *   logp_out[e] = -|z_c - mu'|^2/(2 sigma_i^2 h_i) - D ln(sigma_i sqrt(h_i)) - D/2 ln(2 pi)
  * with mu' from the model's velocity at the stored z_p (/D if MEAN; 0 when
- * sigma_i = 0).  Siblings share one network evaluation of their parent.
+ * sigma_i = 0).  Siblings share one network evaluation of their parent, and
+ * parents of different steps are batched into one network launch (the network
+ * takes a time per sample group), so sparse kept-edge sets still fill the batch.
  *   edge_ids  host [n_edges], strictly ascending global child ids, none a root
  *   logp_out  dev out [n_edges]
  * Synchronises `stream` once while uploading its launch plan. */

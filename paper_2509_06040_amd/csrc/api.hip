@@ -3,6 +3,7 @@
 // evaluated once (Alg. 1, tree-building loop; Sec. 1 "shared prefixes amortize
 // computation").
 #include <algorithm>
+#include <cstring>
 #include <cmath>
 
 #include "common.h"
@@ -45,7 +46,7 @@ Sizes sizes_for(const br_tree* t, const br_model* m, int max_batch) {
     s.n_cond = t->n_tree;
     s.v_rows = max_frontier(t);
     s.partial_floats = (long long)t->n_tree * t->n_leaves * sde_nblk(m->D);
-    s.plan_ints = 6LL * t->n_tree * t->n_nodes + max_batch;
+    s.plan_ints = 9LL * t->n_tree * t->n_nodes + max_batch;
   } else {
     s.n_cond = max_batch;
     s.v_rows = 0;
@@ -100,7 +101,7 @@ extern "C" br_status br_rollout(const br_tree* tree, const br_model* model, cons
     for (int b0 = 0; b0 < Bi; b0 += mb) {
       const int Bc = std::min(mb, Bi - b0);
       if ((s = fill_sample_maps(fb, sm, b0, Bc, v_nodes != nullptr, st)) != BR_OK) return s;
-      if ((s = forward(model, fb, z_nodes, Bc, sched->t[i], cond_tokens, tree->n_tree, v, st)) != BR_OK) return s;
+      if ((s = forward_uniform_t(model, fb, z_nodes, Bc, sched->t[i], tree->n_tree, v, st)) != BR_OK) return s;
     }
     if ((s = launch_sde_step(tree, sched, seed, i, D, v, v_nodes == nullptr, z_nodes, logp_edges, fb.sde_partials,
                              st)) != BR_OK)
@@ -132,35 +133,70 @@ extern "C" br_status br_logprob(const br_tree* tree, const br_model* model, cons
   const Sizes sz = sizes_for(tree, model, mb);
   plan_workspace(model, sz.n_cond, mb, sz.v_rows, sz.partial_floats, sz.plan_ints, &fb, workspace);
 
-  // Launch plan: per step, the unique parents (one network evaluation each, shared by
-  // siblings) and for every edge its child row, parent row, velocity row and output slot.
-  struct StepPlan {
-    std::vector<int> rows, cond, crow, prow, vrow, slot;
-    int o_rows, o_cond, o_crow, o_prow, o_vrow, o_slot;
-  };
-  std::vector<StepPlan> sp(T);
-  for (int e = 0; e < n_edges; ++e) {  // ascending ids: parents of one step come out ascending too
+  // Launch plan.  Parents of kept edges on stochastic steps are evaluated once each (siblings
+  // share the evaluation), ordered by (step, row) and cut into batches of up to mb samples that
+  // may span several steps: the network takes one time per modulation group (condition, step),
+  // so shallow steps with few kept parents do not cost a poorly filled launch each.
+  struct Edge { int step, crow, prow, par, slot; };
+  std::vector<Edge> edges(n_edges);
+  for (int e = 0; e < n_edges; ++e) {
     const int g = edge_ids[e], c = g / nn, n = g - c * nn;
-    const int i = tree->depth[n] - 1, p = c * nn + tree->parent[n];
-    StepPlan& q = sp[i];
-    if (q.rows.empty() || q.rows.back() != p) {
-      q.rows.push_back(p);
-      q.cond.push_back(c);
-    }
-    q.crow.push_back(g);
-    q.prow.push_back(p);
-    q.vrow.push_back((int)q.rows.size() - 1);
-    q.slot.push_back(e);
+    edges[e] = {tree->depth[n] - 1, g, c * nn + tree->parent[n], -1, e};
   }
-  std::vector<int> host;
-  for (int i = 0; i < T; ++i) {
-    StepPlan& q = sp[i];
-    std::vector<int>* arrs[6] = {&q.rows, &q.cond, &q.crow, &q.prow, &q.vrow, &q.slot};
-    int* offs[6] = {&q.o_rows, &q.o_cond, &q.o_crow, &q.o_prow, &q.o_vrow, &q.o_slot};
-    for (int a = 0; a < 6; ++a) {
-      *offs[a] = (int)host.size();
-      host.insert(host.end(), arrs[a]->begin(), arrs[a]->end());
+  std::stable_sort(edges.begin(), edges.end(), [](const Edge& a, const Edge& b) { return a.step < b.step; });
+  std::vector<int> p_row, p_cond, p_step;  // unique parents on stochastic steps
+  for (Edge& ed : edges) {                // ascending ids inside a step: parents ascend too
+    if (!(sched->sigma[ed.step] > 0.f)) continue;
+    if (p_row.empty() || p_row.back() != ed.prow || p_step.back() != ed.step) {
+      p_row.push_back(ed.prow);
+      p_cond.push_back(ed.prow / nn);
+      p_step.push_back(ed.step);
     }
+    ed.par = (int)p_row.size() - 1;
+  }
+  const int n_par = (int)p_row.size();
+  // host image of the plan: [rows | cond | group] per parent, then per batch its group tables,
+  // then [crow | prow | vrow | slot] per edge in (step, id) order
+  std::vector<int> host;
+  const int o_rows = 0, o_cond = n_par, o_group = 2 * n_par;
+  host.resize(3 * (size_t)n_par);
+  struct Batch { int b0, B, o_gcond, o_gt, G; };
+  std::vector<Batch> batches;
+  for (int b0 = 0; b0 < n_par; b0 += mb) {
+    Batch bt{b0, std::min(mb, n_par - b0), 0, 0, 0};
+    std::vector<int> gcond, gstep;
+    for (int i = b0; i < b0 + bt.B; ++i) {
+      int g = -1;
+      for (int k = (int)gcond.size() - 1; k >= 0 && g < 0; --k)
+        if (gcond[k] == p_cond[i] && gstep[k] == p_step[i]) g = k;
+      if (g < 0) {
+        gcond.push_back(p_cond[i]);
+        gstep.push_back(p_step[i]);
+        g = (int)gcond.size() - 1;
+      }
+      host[o_rows + i] = p_row[i];
+      host[o_cond + i] = p_cond[i];
+      host[o_group + i] = g;
+    }
+    bt.G = (int)gcond.size();
+    bt.o_gcond = (int)host.size();
+    host.insert(host.end(), gcond.begin(), gcond.end());
+    bt.o_gt = (int)host.size();
+    for (int k = 0; k < bt.G; ++k) {
+      const float tv = sched->t[gstep[k]];
+      int bits;
+      std::memcpy(&bits, &tv, sizeof(bits));
+      host.push_back(bits);
+    }
+    batches.push_back(bt);
+  }
+  const int o_crow = (int)host.size(), o_prow = o_crow + n_edges, o_vrow = o_prow + n_edges, o_slot = o_vrow + n_edges;
+  host.resize(host.size() + 4 * (size_t)n_edges);
+  for (int e = 0; e < n_edges; ++e) {
+    host[o_crow + e] = edges[e].crow;
+    host[o_prow + e] = edges[e].prow;
+    host[o_vrow + e] = edges[e].par >= 0 ? edges[e].par % mb : 0;  // row of the batch's velocity buffer
+    host[o_slot + e] = edges[e].slot;
   }
   BR_REQUIRE((long long)host.size() <= sz.plan_ints, BR_EWORKSPACE, "br_logprob: plan does not fit the workspace");
   BR_HIP(hipMemcpyAsync(fb.plan, host.data(), host.size() * sizeof(int), hipMemcpyHostToDevice, st));
@@ -168,21 +204,37 @@ extern "C" br_status br_logprob(const br_tree* tree, const br_model* model, cons
 
   if ((s = embed_cond(model, fb, cond_tokens, tree->n_tree, st)) != BR_OK) return s;
   const long long D = model->D;
-  for (int i = 0; i < T; ++i) {
-    const StepPlan& q = sp[i];
-    const int ne = (int)q.crow.size(), np = (int)q.rows.size();
-    if (ne == 0) continue;
-    if (sched->sigma[i] > 0.f) {
-      const SampleMap sm{fb.plan + q.o_rows, fb.plan + q.o_cond, 0, 0, 1};
-      for (int b0 = 0; b0 < np; b0 += mb) {
-        const int Bc = std::min(mb, np - b0);
-        if ((s = fill_sample_maps(fb, sm, b0, Bc, 0, st)) != BR_OK) return s;
-        if ((s = forward(model, fb, z_nodes, Bc, sched->t[i], cond_tokens, tree->n_tree, fb.v, st)) != BR_OK) return s;
-      }
-    }
-    if ((s = launch_logp_eval(sched, i, D, z_nodes, fb.v, fb.plan + q.o_crow, fb.plan + q.o_prow, fb.plan + q.o_vrow,
-                              fb.plan + q.o_slot, ne, logp_out, fb.sde_partials, st)) != BR_OK)
+  auto eval_range = [&](int e0, int e1) {  // edges [e0, e1): one step, velocities (if any) in fb.v
+    return launch_logp_eval(sched, edges[e0].step, D, z_nodes, fb.v, fb.plan + o_crow + e0, fb.plan + o_prow + e0,
+                            fb.plan + o_vrow + e0, fb.plan + o_slot + e0, e1 - e0, logp_out, fb.sde_partials, st);
+  };
+  // deterministic steps: no evaluation, log-prob 0
+  for (int e0 = 0; e0 < n_edges;) {
+    int e1 = e0 + 1;
+    while (e1 < n_edges && edges[e1].step == edges[e0].step) ++e1;
+    if (edges[e0].par < 0 && (s = eval_range(e0, e1)) != BR_OK) return s;
+    e0 = e1;
+  }
+  int e_next = 0;  // edges are in (step, parent) order, so each batch owns a contiguous range
+  for (const Batch& bt : batches) {
+    SampleMap sm{fb.plan + o_rows, fb.plan + o_cond, 0, 0, 1};
+    sm.group = fb.plan + o_group;
+    if ((s = fill_sample_maps(fb, sm, bt.b0, bt.B, 2, st)) != BR_OK) return s;
+    if ((s = forward(model, fb, z_nodes, bt.B, fb.plan + bt.o_gcond, reinterpret_cast<const float*>(fb.plan + bt.o_gt),
+                     bt.G, fb.v, st)) != BR_OK)
       return s;
+    while (e_next < n_edges && edges[e_next].par < bt.b0 + bt.B) {
+      if (edges[e_next].par < 0) {  // deterministic step, done above
+        ++e_next;
+        continue;
+      }
+      int e1 = e_next + 1;
+      while (e1 < n_edges && edges[e1].step == edges[e_next].step && edges[e1].par >= 0 &&
+             edges[e1].par < bt.b0 + bt.B)
+        ++e1;
+      if ((s = eval_range(e_next, e1)) != BR_OK) return s;
+      e_next = e1;
+    }
   }
   return BR_OK;
 }
@@ -215,7 +267,7 @@ extern "C" br_status br_velocity(const br_model* model, const float* z, float t,
   for (int b0 = 0; b0 < B; b0 += mb) {
     const int Bc = std::min(mb, B - b0);
     if ((s = fill_sample_maps(fb, sm, b0, Bc, 0, st)) != BR_OK) return s;
-    if ((s = forward(model, fb, z, Bc, t, cond_tokens, n_cond, v_out, st)) != BR_OK) return s;
+    if ((s = forward_uniform_t(model, fb, z, Bc, t, n_cond, v_out, st)) != BR_OK) return s;
   }
   return BR_OK;
 }

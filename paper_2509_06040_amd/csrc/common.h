@@ -36,6 +36,7 @@ struct SampleMap {
   const int* rows;  // dev or nullptr
   const int* cond;  // dev or nullptr
   int n_nodes, off, width;
+  const int* group = nullptr;  // dev or nullptr: modulation group of a sample (default: its condition)
 };
 
 }  // namespace br

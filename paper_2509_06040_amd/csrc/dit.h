@@ -43,9 +43,12 @@ struct EpiArgs {
 
 struct FwdBuffers {  // carved from the workspace
   int* rowmap;
-  int* condmap;
+  int* condmap;   // sample -> condition (its condition tokens)
+  int* modmap;    // sample -> modulation group (its adaLN vectors)
   int* vrows;
-  float *temb, *h1, *ct, *pooled, *cvec, *mods, *cond_emb, *x, *sde_partials;
+  int* gcond;     // modulation group -> condition
+  float* gt;      // modulation group -> time
+  float *temb, *h1, *ct, *pooled, *pool_lin, *cvec, *mods, *cond_emb, *x, *sde_partials;
   void *patches, *xn, *qkv, *hid;
   float* v;       // compact velocity [max_frontier, D] (rollout only)
   int* plan;      // br_logprob launch plan
@@ -55,11 +58,16 @@ struct FwdBuffers {  // carved from the workspace
 size_t plan_workspace(const br_model* m, int n_cond, int max_batch, long long v_rows, long long partial_floats,
                       long long plan_ints, FwdBuffers* fb, void* base);
 
-// One network evaluation of `B` samples (B <= max_batch of the plan).
-// z_base: latent rows; smap: sample -> (row, cond); v_out rows given by fb.vrows.
-br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, float t,
-                  const void* cond_tokens, int n_cond, float* v_out, hipStream_t st);
-// Fill rowmap/condmap/vrows for a batch [b0, b0+B) of a frontier.
+// One network evaluation of `B` samples (B <= max_batch of the plan).  z_base: latent rows,
+// picked by fb.rowmap; v_out rows given by fb.vrows.  The adaLN vectors are computed once per
+// modulation group g = (condition gcond[g], time gt[g]), g < n_groups <= max(n_cond, max_batch);
+// sample b uses group fb.modmap[b].  gcond / gt are device arrays.
+br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, const int* gcond,
+                  const float* gt, int n_groups, float* v_out, hipStream_t st);
+// The same with one time for the whole batch: one group per condition, modmap = condmap.
+br_status forward_uniform_t(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, float t, int n_cond,
+                            float* v_out, hipStream_t st);
+// Fill rowmap/condmap/modmap/vrows for a batch [b0, b0+B) of a frontier.
 br_status fill_sample_maps(const FwdBuffers& fb, const SampleMap& smap, int b0, int B, int v_mode_rows, hipStream_t st);
 // Condition-token embedding, once per call.
 br_status embed_cond(const br_model* m, const FwdBuffers& fb, const void* cond_tokens, int n_cond, hipStream_t st);

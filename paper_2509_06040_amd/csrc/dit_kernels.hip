@@ -13,14 +13,24 @@ __device__ inline float to_f(T v) { return (float)v; }
 
 // ------------------------------------------------------------- sample maps
 __global__ void sample_map_kernel(SampleMap sm, int b0, int B, int v_rows_mode, int* __restrict__ rowmap,
-                                  int* __restrict__ condmap, int* __restrict__ vrows) {
+                                  int* __restrict__ condmap, int* __restrict__ modmap, int* __restrict__ vrows) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B) return;
   const int b = b0 + i;
   const int row = sm.rows ? sm.rows[b] : (b / sm.width) * sm.n_nodes + sm.off + b % sm.width;
+  const int c = sm.cond ? sm.cond[b] : b / sm.width;
   rowmap[i] = row;
-  condmap[i] = sm.cond ? sm.cond[b] : b / sm.width;
-  vrows[i] = v_rows_mode ? row : b;
+  condmap[i] = c;
+  modmap[i] = sm.group ? sm.group[b] : c;
+  vrows[i] = v_rows_mode == 1 ? row : (v_rows_mode == 2 ? i : b);  // arena row / row of this batch / frontier index
+}
+
+// One modulation group per condition, all at time t.
+__global__ void uniform_groups_kernel(float t, int n_cond, int* __restrict__ gcond, float* __restrict__ gt) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_cond) return;
+  gcond[g] = g;
+  gt[g] = t;
 }
 
 // ---------------------------------------------------------------- patchify
@@ -59,15 +69,26 @@ __global__ __launch_bounds__(256) void cond_broadcast_kernel(const float* __rest
 // ------------------------------------------------------- conditioning path
 // temb = [cos(1000 t f_k), sin(1000 t f_k)], f_k = 10000^(-k/128).  The angle (up to 1000 rad)
 // is formed and reduced to [-pi, pi] in fp64, then fp32 sin/cos suffice.
-__global__ __launch_bounds__(128) void temb_kernel(float t, float* __restrict__ temb) {
-  const int k = threadIdx.x;
+__device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
+
+__global__ __launch_bounds__(128) void temb_kernel(const float* __restrict__ gt, float* __restrict__ temb) {
+  const int k = threadIdx.x, g = blockIdx.x;
   const double f = exp(-9.210340371976184 * (double)k / 128.0);  // ln 10000
-  double a = 1000.0 * (double)t * f;
+  double a = 1000.0 * (double)gt[g] * f;
   a -= 6.283185307179586 * rint(a * 0.15915494309189535);
   float sn, cs;
   sincosf((float)a, &sn, &cs);
-  temb[k] = cs;
-  temb[128 + k] = sn;
+  temb[(size_t)g * 256 + k] = cs;
+  temb[(size_t)g * 256 + 128 + k] = sn;
+}
+
+// cvec[g, :] = silu(pool_lin[gcond[g], :] + ct[g, :])
+__global__ __launch_bounds__(256) void group_cvec_kernel(const float* __restrict__ pool_lin,
+                                                         const float* __restrict__ ct, const int* __restrict__ gcond,
+                                                         int H, float* __restrict__ cvec) {
+  const int g = blockIdx.y, h = blockIdx.x * 256 + threadIdx.x;
+  if (h >= H) return;
+  cvec[(size_t)g * H + h] = silu_f(pool_lin[(size_t)gcond[g] * H + h] + ct[(size_t)g * H + h]);
 }
 
 // pooled[c, :] = mean over the condition tokens of condition c (depends on the prompt only)
@@ -80,8 +101,6 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ cond, i
   for (int j = 0; j < Nc; ++j) s += to_f(cond[((size_t)c * Nc + j) * cd + d]);
   pooled[(size_t)c * cd + d] = s / (float)Nc;
 }
-
-__device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
 template <typename TW>
 struct WChunk;  // eight consecutive weights as floats
@@ -170,22 +189,37 @@ static br_status skinny(const float* in, int ldi, int R, const TW* W, int K, int
   return BR_OK;
 }
 
-// cvec = t_mlp(temb) + pool_lin(pooled); mods = ada_lin(silu(cvec))
+// Per modulation group g: cvec = silu(t_mlp(temb(gt[g])) + pool_lin[gcond[g]]); mods = ada_lin(cvec).
 template <typename T>
-static br_status conditioning_t(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond,
+static br_status conditioning_t(const br_model* m, const FwdBuffers& fb, const int* gcond, const float* gt, int G,
                                 hipStream_t st) {
   const int H = m->H;
-  hipLaunchKernelGGL(temb_kernel, dim3(1), dim3(128), 0, st, t, fb.temb);
+  hipLaunchKernelGGL(temb_kernel, dim3(G), dim3(128), 0, st, gt, fb.temb);
   BR_LAUNCH_CHECK();
   br_status s;
-  if ((s = skinny<T>(fb.temb, 256, 1, (const T*)m->w[BR_W_T1_W], 256, H, (const float*)m->w[BR_W_T1_B], nullptr, 0, 1,
+  if ((s = skinny<T>(fb.temb, 256, G, (const T*)m->w[BR_W_T1_W], 256, H, (const float*)m->w[BR_W_T1_B], nullptr, 0, 1,
                      fb.h1, H, st)) != BR_OK) return s;
-  if ((s = skinny<T>(fb.h1, H, 1, (const T*)m->w[BR_W_T2_W], H, H, (const float*)m->w[BR_W_T2_B], nullptr, 0, 0, fb.ct,
+  if ((s = skinny<T>(fb.h1, H, G, (const T*)m->w[BR_W_T2_W], H, H, (const float*)m->w[BR_W_T2_B], nullptr, 0, 0, fb.ct,
                      H, st)) != BR_OK) return s;
-  if ((s = skinny<T>(fb.pooled, m->cd, n_cond, (const T*)m->w[BR_W_POOL_W], m->cd, H, (const float*)m->w[BR_W_POOL_B],
-                     fb.ct, 0, 1, fb.cvec, H, st)) != BR_OK) return s;  // cvec holds silu(cvec)
-  return skinny<T>(fb.cvec, H, n_cond, (const T*)m->w[BR_W_ADA_W], H, m->A, (const float*)m->w[BR_W_ADA_B], nullptr, 0,
-                   0, fb.mods, m->A, st);
+  hipLaunchKernelGGL(group_cvec_kernel, dim3(cdiv(H, 256), G), dim3(256), 0, st, fb.pool_lin, fb.ct, gcond, H, fb.cvec);
+  BR_LAUNCH_CHECK();
+  return skinny<T>(fb.cvec, H, G, (const T*)m->w[BR_W_ADA_W], H, m->A, (const float*)m->w[BR_W_ADA_B], nullptr, 0, 0,
+                   fb.mods, m->A, st);
+}
+
+// pool_lin[c, :] = W_pool pooled[c, :] + b_pool: the time-independent half of the conditioning vector
+br_status launch_pool_linear(const br_model* m, const FwdBuffers& fb, int n_cond, hipStream_t st) {
+  if (m->cfg.dtype == BR_BF16)
+    return skinny<bf16>(fb.pooled, m->cd, n_cond, (const bf16*)m->w[BR_W_POOL_W], m->cd, m->H,
+                        (const float*)m->w[BR_W_POOL_B], nullptr, 0, 0, fb.pool_lin, m->H, st);
+  return skinny<float>(fb.pooled, m->cd, n_cond, (const float*)m->w[BR_W_POOL_W], m->cd, m->H,
+                       (const float*)m->w[BR_W_POOL_B], nullptr, 0, 0, fb.pool_lin, m->H, st);
+}
+
+br_status launch_uniform_groups(const FwdBuffers& fb, float t, int n_cond, hipStream_t st) {
+  hipLaunchKernelGGL(uniform_groups_kernel, dim3(cdiv(n_cond, 256)), dim3(256), 0, st, t, n_cond, fb.gcond, fb.gt);
+  BR_LAUNCH_CHECK();
+  return BR_OK;
 }
 
 br_status launch_pool(const br_model* m, const FwdBuffers& fb, const void* cond, int n_cond, hipStream_t st) {
@@ -198,9 +232,10 @@ br_status launch_pool(const br_model* m, const FwdBuffers& fb, const void* cond,
   return BR_OK;
 }
 
-br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st) {
-  return m->cfg.dtype == BR_BF16 ? conditioning_t<bf16>(m, fb, t, cond, n_cond, st)
-                                 : conditioning_t<float>(m, fb, t, cond, n_cond, st);
+br_status conditioning(const br_model* m, const FwdBuffers& fb, const int* gcond, const float* gt, int G,
+                       hipStream_t st) {
+  return m->cfg.dtype == BR_BF16 ? conditioning_t<bf16>(m, fb, gcond, gt, G, st)
+                                 : conditioning_t<float>(m, fb, gcond, gt, G, st);
 }
 
 // ------------------------------------------------------- LayerNorm-modulate
@@ -438,7 +473,7 @@ br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, 
 // -------------------------------------------------------------- launchers
 br_status fill_sample_maps(const FwdBuffers& fb, const SampleMap& smap, int b0, int B, int v_mode_rows, hipStream_t st) {
   hipLaunchKernelGGL(sample_map_kernel, dim3(cdiv(B, 256)), dim3(256), 0, st, smap, b0, B, v_mode_rows, fb.rowmap,
-                     fb.condmap, fb.vrows);
+                     fb.condmap, fb.modmap, fb.vrows);
   BR_LAUNCH_CHECK();
   return BR_OK;
 }

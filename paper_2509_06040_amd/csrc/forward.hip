@@ -1,4 +1,5 @@
 // Model handle, workspace plan and one evaluation of the velocity network.
+#include <algorithm>
 #include <new>
 
 #include "common.h"
@@ -7,7 +8,10 @@
 #include "prof.h"
 
 namespace br {
-br_status conditioning(const br_model* m, const FwdBuffers& fb, float t, const void* cond, int n_cond, hipStream_t st);
+br_status conditioning(const br_model* m, const FwdBuffers& fb, const int* gcond, const float* gt, int G,
+                       hipStream_t st);
+br_status launch_pool_linear(const br_model* m, const FwdBuffers& fb, int n_cond, hipStream_t st);
+br_status launch_uniform_groups(const FwdBuffers& fb, float t, int n_cond, hipStream_t st);
 br_status launch_patchify(const br_model* m, const FwdBuffers& fb, const float* z, int B, hipStream_t st);
 br_status launch_cond_broadcast(const br_model* m, const FwdBuffers& fb, int B, hipStream_t st);
 br_status launch_pool(const br_model* m, const FwdBuffers& fb, const void* cond, int n_cond, hipStream_t st);
@@ -25,15 +29,20 @@ size_t plan_workspace(const br_model* m, int n_cond, int max_batch, long long v_
   };
   const size_t B = (size_t)max_batch, H = m->H, L = m->L, es = esize(m);
   FwdBuffers f;
+  const size_t G = std::max<size_t>(B, (size_t)n_cond);  // modulation groups: at most one per sample
   f.rowmap = (int*)take(B * 4);
   f.condmap = (int*)take(B * 4);
+  f.modmap = (int*)take(B * 4);
   f.vrows = (int*)take(B * 4);
-  f.temb = (float*)take(256 * 4);
-  f.h1 = (float*)take(H * 4);
-  f.ct = (float*)take(H * 4);
+  f.gcond = (int*)take(G * 4);
+  f.gt = (float*)take(G * 4);
+  f.temb = (float*)take(G * 256 * 4);
+  f.h1 = (float*)take(G * H * 4);
+  f.ct = (float*)take(G * H * 4);
   f.pooled = (float*)take((size_t)n_cond * m->cd * 4);
-  f.cvec = (float*)take((size_t)n_cond * H * 4);
-  f.mods = (float*)take((size_t)n_cond * m->A * 4);
+  f.pool_lin = (float*)take((size_t)n_cond * H * 4);
+  f.cvec = (float*)take(G * H * 4);
+  f.mods = (float*)take(G * m->A * 4);
   f.cond_emb = (float*)take((size_t)n_cond * m->Nc * H * 4);
   f.x = (float*)take(B * L * H * 4);
   f.patches = take(B * m->n_img * m->pd * es);
@@ -55,17 +64,26 @@ br_status embed_cond(const br_model* m, const FwdBuffers& fb, const void* cond_t
   ea.bias = (const float*)m->w[BR_W_COND_B];
   ea.out = fb.cond_emb;
   ea.ldo = m->H;
-  return launch_gemm(m->cfg.dtype, EPI_BIAS_F32, cond_tokens, m->cd, m->w[BR_W_COND_W], m->cd, n_cond * m->Nc, m->H,
-                     m->cd, ea, st);
+  if ((sp = launch_gemm(m->cfg.dtype, EPI_BIAS_F32, cond_tokens, m->cd, m->w[BR_W_COND_W], m->cd, n_cond * m->Nc,
+                        m->H, m->cd, ea, st)) != BR_OK)
+    return sp;
+  return launch_pool_linear(m, fb, n_cond, st);
 }
 
-br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, float t, const void* cond_tokens,
-                  int n_cond, float* v_out, hipStream_t st) {
+br_status forward_uniform_t(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, float t, int n_cond,
+                            float* v_out, hipStream_t st) {
+  br_status s = launch_uniform_groups(fb, t, n_cond, st);
+  if (s != BR_OK) return s;
+  return forward(m, fb, z_base, B, fb.gcond, fb.gt, n_cond, v_out, st);
+}
+
+br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, int B, const int* gcond,
+                  const float* gt, int n_groups, float* v_out, hipStream_t st) {
   const int H = m->H, L = m->L, dt = m->cfg.dtype;
   const size_t es = esize(m);
   br_status s;
 #define BR_TRY(x) do { if ((s = (x)) != BR_OK) return s; } while (0)
-  BR_TRY(conditioning(m, fb, t, cond_tokens, n_cond, st));
+  BR_TRY(conditioning(m, fb, gcond, gt, n_groups, st));
   BR_TRY(launch_patchify(m, fb, z_base, B, st));
   {
     EpiArgs ea{};
@@ -87,7 +105,7 @@ br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, 
     const char* proj_w = (const char*)m->w[BR_W_PROJ_W] + (size_t)k * H * H * es;
     const char* fc1_w = (const char*)m->w[BR_W_FC1_W] + (size_t)k * m->R * H * H * es;
     const char* fc2_w = (const char*)m->w[BR_W_FC2_W] + (size_t)k * m->R * H * H * es;
-    BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, M, L, L, H, fb.mods, m->A, mo, mo + H, fb.condmap, st));
+    BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, M, L, L, H, fb.mods, m->A, mo, mo + H, fb.modmap, st));
     {
       EpiArgs ea{};
       ea.bias = (const float*)m->w[BR_W_QKV_B] + (size_t)k * 3 * H;
@@ -104,11 +122,11 @@ br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, 
       ea.mods = fb.mods;
       ea.A = m->A;
       ea.gate_off = mo + 2 * H;
-      ea.condmap = fb.condmap;
+      ea.condmap = fb.modmap;
       ea.L = L;
       BR_TRY(launch_gemm(dt, EPI_BIAS_GATE_RES, fb.xn, H, proj_w, H, M, H, H, ea, st));
     }
-    BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, M, L, L, H, fb.mods, m->A, mo + 3 * H, mo + 4 * H, fb.condmap, st));
+    BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, M, L, L, H, fb.mods, m->A, mo + 3 * H, mo + 4 * H, fb.modmap, st));
     {
       EpiArgs ea{};
       ea.bias = (const float*)m->w[BR_W_FC1_B] + (size_t)k * m->R * H;
@@ -124,13 +142,13 @@ br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, 
       ea.mods = fb.mods;
       ea.A = m->A;
       ea.gate_off = mo + 5 * H;
-      ea.condmap = fb.condmap;
+      ea.condmap = fb.modmap;
       ea.L = L;
       BR_TRY(launch_gemm(dt, EPI_BIAS_GATE_RES, fb.hid, m->R * H, fc2_w, m->R * H, M, H, m->R * H, ea, st));
     }
   }
   const int mo = m->NB * 6 * H;
-  BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, B * m->n_img, m->n_img, L, H, fb.mods, m->A, mo, mo + H, fb.condmap, st));
+  BR_TRY(launch_ln_modulate(dt, fb.x, fb.xn, B * m->n_img, m->n_img, L, H, fb.mods, m->A, mo, mo + H, fb.modmap, st));
   {
     EpiArgs ea{};
     const br_model_cfg& c = m->cfg;

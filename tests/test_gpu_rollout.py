@@ -169,6 +169,32 @@ def test_hybrid_ode_sde_schedule_end_to_end(lib):
     assert np.all(np.abs(host(out) - ref) <= 1e-3 * np.abs(ref))
 
 
+def test_logprob_batches_spanning_and_cutting_steps(lib):
+    """The re-evaluation batches parents across steps (one time per modulation group); with a
+    workspace for 3 samples at a time the batches both span several steps and cut steps in two."""
+    wl = synth.WORKLOADS["tiny"]
+    C = 2
+    r = _run_rollout(wl, C, 21, [0, 1], ode_steps=(3,))
+    t, cfg, W, cond, sched, D = r["t"], r["cfg"], r["W"], r["cond"], r["sched"], r["D"]
+    o = tree.tree_build(wl["T"], wl["splits"], wl["K"])
+    W2 = synth.perturb_weights(cfg, W, 5, 0.01)
+    model2 = make_model(cfg, W2)
+    rng = np.random.default_rng(0)
+    all_edges = np.array([c * t.n_nodes + n for c in range(C) for n in range(1, t.n_nodes)], np.int32)
+    ids = np.sort(rng.choice(all_edges, size=len(all_edges) * 2 // 3, replace=False)).astype(np.int32)
+    vel2 = lambda zz, tt, ci: dit.forward(cfg, W2, zz, tt, cond, ci)
+    z = host(r["z"])
+    ref = rollout.edge_logprob(o, vel2, sched, z.astype(np.float64), ids, C)
+    for max_batch in (3, C * t.n_leaves):
+        ws = bytes_buffer(br.workspace_bytes(t, model2, max_batch))
+        out = torch.full((len(ids),), 7.0, device=DEV)
+        br.logprob(t, model2, sched, cond_dev(cfg, cond), r["z"], ids, out, ws)
+        got = host(out)
+        ode = np.array([t.depth[g % t.n_nodes] - 1 == 3 for g in ids])
+        assert np.all(got[ode] == 0.0) and np.all(ref[ode] == 0.0)
+        assert np.all(np.abs(got[~ode] - ref[~ode]) <= 1e-3 * np.abs(ref[~ode])), max_batch
+
+
 def test_rollout_rejects_bad_arguments(lib):
     wl = synth.WORKLOADS["tiny"]
     r = _run_rollout(wl, 1, 3, [0])
