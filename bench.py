@@ -37,20 +37,20 @@ TILE_NAMES = {4: "256x256 lds-direct", 5: "128x128 lds-direct",
 # see profiles/hot_kernels_hbm_traffic.md.  Valid only for the kernel sources hashed below.
 TRAFFIC = {
     "gemm_bf16[bias_gate_residual,256x256 persistent stream]": dict(
-        bytes_per_launch=192294.46 * 1024 * 2.0 + 119117.72 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="2f57965a9c539575b187b1d1a2c67b30a2e5919e"),
+        bytes_per_launch=283328.01 * 1024 * 2.0 + 177334.40 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="7daeaca5e0c910e3eda6b815841cebd05c2f0a46"),
     "gemm_bf16[bias_gelu,256x256 persistent stream]": dict(
-        bytes_per_launch=279120.27 * 1024 * 2.0 + 219522.46 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="2f57965a9c539575b187b1d1a2c67b30a2e5919e"),
+        bytes_per_launch=383608.90 * 1024 * 2.0 + 309670.74 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="7daeaca5e0c910e3eda6b815841cebd05c2f0a46"),
     "gemm_bf16[bias,256x256 persistent stream]": dict(
-        bytes_per_launch=157553.37 * 1024 * 2.0 + 126248.00 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="2f57965a9c539575b187b1d1a2c67b30a2e5919e"),
+        bytes_per_launch=264978.79 * 1024 * 2.0 + 189372.00 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="7daeaca5e0c910e3eda6b815841cebd05c2f0a46"),
     "attn_bf16[d64]": dict(
-        bytes_per_launch=63240.37 * 1024 * 2.0 + 42082.67 * 1024 * 1.0,
+        bytes_per_launch=94801.87 * 1024 * 2.0 + 63124.00 * 1024 * 1.0,
         sources=('attn_bf16.hip',), sha1="326b4d101e6726f9589016066504c0c1355e2dd3"),
     "ln_modulate": dict(
-        bytes_per_launch=42116.91 * 1024 * 2.0 + 41964.94 * 1024 * 1.0,
-        sources=('dit_kernels.hip',), sha1="7fc6453ed298939f548883bec24304ec782964b2"),
+        bytes_per_launch=63168.13 * 1024 * 2.0 + 62947.41 * 1024 * 1.0,
+        sources=('dit_kernels.hip',), sha1="6169a0553b7a182216bf177b290d38a6ac4052ed"),
 }
 
 
