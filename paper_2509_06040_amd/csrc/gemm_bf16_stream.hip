@@ -196,11 +196,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   // After the reads of the last step have been issued and have arrived, the other stage must
   // have landed too (nothing younger is in flight); one barrier then makes both true for every
   // wave, the freed stage is refilled, and the first fragments of the other stage are read.
-  // `stores_behind`: the wave has issued at least EPILOGUE_STORES stores since the fetch of the
+  // `stores_behind`: the wave has issued at least that many stores since the fetch of the
   // other stage (the epilogue of a tile wholly inside the matrix).  Memory operations retire in
   // issue order, so the other stage has landed once no more than that many are outstanding,
   // and the stores' write acknowledgements need not be waited for yet.
-  auto stage_step = [&](auto S, int q, bool stores_behind) {
+  auto stage_step = [&](auto S, int q, int stores_behind) {
     constexpr int CUR = decltype(S)::value, NXT = CUR ^ 1;
     const char* cur = g_ring<CUR>;
 #pragma unroll
@@ -210,8 +210,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
       mma(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (stores_behind)
+    if (stores_behind >= EPILOGUE_STORES)
       asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(EPILOGUE_STORES) : "memory");
+    else if (stores_behind >= EPILOGUE_STORES / 2)
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(EPILOGUE_STORES / 2) : "memory");
     else
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -233,17 +235,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
   read_frags(g_ring<0>, 0, 0);
 
   char* ebuf = g_epi + wv * 4096;
-  bool stores_behind = false;
+  int stores_behind = 0;
   for (;;) {
     stage_step(I0{}, 0, stores_behind);
-    stage_step(I1{}, 1, false);
+    stage_step(I1{}, 1, 0);
     for (int q = 2; q < nst; q += 2) {
-      stage_step(I0{}, q, false);
-      stage_step(I1{}, q + 1, false);
+      stage_step(I0{}, q, 0);
+      stage_step(I1{}, q + 1, 0);
     }
     // ---- epilogue of tile (tm, tn); the next tile's first stages keep landing meanwhile
-    stores_behind = wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, tm * BM + wm0, tn * BN + wn0, M, N, epi, lane) >=
-                    EPILOGUE_STORES;
+    stores_behind = wave_epilogue<TM, TN, MODE, TOUT>(acc, ebuf, tm * BM + wm0, tn * BN + wn0, M, N, epi, lane);
     zero_acc();
     if (!has_next) break;
     // read the next tile's first fragments again rather than keep them alive across the

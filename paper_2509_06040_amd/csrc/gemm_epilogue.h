@@ -11,6 +11,8 @@
 // offset) are fetched once before the first store, and the per-row addend (residual stream,
 // position embedding) is fetched ADDEND_AHEAD passes ahead of its use.
 #pragma once
+#include <type_traits>
+
 #include "dit.h"
 
 namespace br {
@@ -128,6 +130,55 @@ __device__ inline void wave_epilogue_pair(const f32x16_e (&acc)[TN][TM], char* e
   }
 }
 
+// bf16 outputs (bias, bias + GELU) of a wave tile wholly inside the matrix: bias and activation
+// are applied in the accumulator layout and the values are rounded to bf16 BEFORE the trip through
+// LDS, which halves the LDS traffic and lets a pass cover 32 rows: per pass 8 x ds_write_b64 by
+// every lane, 4 x ds_read_b128, 4 stores of 16 bytes per lane (8 rows x 128 bytes each).  A buffer
+// row is 128 bytes = eight 16-byte chunks, chunk c of row r sits in slot c ^ ((r >> 1) & 7).
+template <int TM, int TN, int MODE>
+__device__ inline void wave_epilogue_bf16_full(const f32x16_e (&acc)[TN][TM], char* ebuf, int m_base, int n_base,
+                                               const Epilogue<MODE, bf16>& epi, int lane) {
+  static_assert(MODE == EPI_BIAS || MODE == EPI_BIAS_GELU, "plain bf16 outputs only");
+  typedef __bf16 bf16x4_e __attribute__((ext_vector_type(4)));
+  typedef unsigned int u32x4_e __attribute__((ext_vector_type(4)));
+  const int l32 = lane & 31, lh = lane >> 5;
+  float4 bias[TN][4];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) bias[i][g] = epi.bias4(n_base + i * 32 + g * 8 + lh * 4);
+  const int wswz = (l32 >> 1) & 7;
+  char* wrow = ebuf + l32 * 128 + lh * 8;
+  const int rrow = lane >> 3, rc = lane & 7;  // this lane reads chunk rc of rows rrow + 8 q
+  bf16* const obase = reinterpret_cast<bf16*>(epi.a.out) + (long long)(m_base + rrow) * epi.a.ldo + n_base + rc * 8;
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    epilogue_wave_fence();
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float v0 = acc[i][j][4 * g] + bias[i][g].x, v1 = acc[i][j][4 * g + 1] + bias[i][g].y,
+              v2 = acc[i][j][4 * g + 2] + bias[i][g].z, v3 = acc[i][j][4 * g + 3] + bias[i][g].w;
+        if (MODE == EPI_BIAS_GELU) {
+          v0 = gelu_tanh_f(v0);
+          v1 = gelu_tanh_f(v1);
+          v2 = gelu_tanh_f(v2);
+          v3 = gelu_tanh_f(v3);
+        }
+        const bf16x4_e pk = {(bf16)v0, (bf16)v1, (bf16)v2, (bf16)v3};
+        *reinterpret_cast<bf16x4_e*>(wrow + (((i * 4 + g) ^ wswz) << 4)) = pk;
+      }
+    epilogue_wave_fence();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = rrow + 8 * q;
+      const u32x4_e v = *reinterpret_cast<const u32x4_e*>(ebuf + r * 128 + ((rc ^ ((r >> 1) & 7)) << 4));
+      *reinterpret_cast<u32x4_e*>(obase + (long long)(j * 32 + 8 * q) * epi.a.ldo) = v;
+    }
+  }
+}
+
 // Returns a lower bound on the number of store instructions the wave has issued (every lane
 // active): 4 per 16-row pass on the branch-free path, unknown (0) on the guarded ones.
 template <int TM, int TN, int MODE, typename TOUT>
@@ -138,8 +189,13 @@ __device__ inline int wave_epilogue(const f32x16_e (&acc)[TN][TM], char* ebuf, i
   if (rps > 0 && rps < TM * 32) {
     wave_epilogue_rows<TM, TN, MODE, TOUT>(acc, ebuf, m_base, n_base, M, N, epi, lane);
   } else if (m_base + TM * 32 <= M && n_base + TN * 32 <= N) {
-    wave_epilogue_pair<true, TM, TN, MODE, TOUT>(acc, ebuf, m_base, n_base, M, N, epi, lane);
-    return TM * 2 * 4;
+    if constexpr ((MODE == EPI_BIAS || MODE == EPI_BIAS_GELU) && std::is_same<TOUT, bf16>::value) {
+      wave_epilogue_bf16_full<TM, TN, MODE>(acc, ebuf, m_base, n_base, epi, lane);
+      return TM * 4;
+    } else {
+      wave_epilogue_pair<true, TM, TN, MODE, TOUT>(acc, ebuf, m_base, n_base, M, N, epi, lane);
+      return TM * 2 * 4;
+    }
   } else {
     wave_epilogue_pair<false, TM, TN, MODE, TOUT>(acc, ebuf, m_base, n_base, M, N, epi, lane);
   }
