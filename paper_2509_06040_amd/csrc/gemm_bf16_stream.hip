@@ -11,11 +11,13 @@
 // barrier of the stage.  Measured with the math in the loop, one 64 KB stage in
 // flight beats three 32 KB stages in flight.
 //
-// Epilogue: the MFMA accumulator layout gives a lane 4 consecutive columns of ONE
-// row, which would make every store instruction touch 32 different rows.  Each wave
-// therefore passes its accumulators through a private 4 KB LDS buffer, 16 rows at a
-// time (16-byte columns XOR-swizzled by the row, conflict-free both ways), and
-// writes rows of 64 consecutive columns: 16 lanes x 16 bytes per row.
+// Operand loads of a tile wholly inside the matrix take a scalar block address and one of two
+// constant per-lane offsets, so the k-loop issues no vector arithmetic beside the MFMAs (the
+// two do not overlap on this hardware).
+//
+// Epilogue (gemm_epilogue.h): the MFMA accumulator layout gives a lane 4 consecutive columns
+// of ONE row, which would make every store instruction touch 32 different rows.  Each wave
+// therefore passes its tile through a private 4 KB LDS buffer and writes whole row segments.
 //
 // Requirements: K % 128 == 0 (every tile starts on ring slot 0), K >= 128, operands below 4 GiB.
 #include <type_traits>

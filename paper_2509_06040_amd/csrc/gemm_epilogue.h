@@ -1,12 +1,13 @@
 // Epilogue of the MFMA GEMM kernels, shared by all tile shapes whose waves own 64 output
 // columns.  The 32x32 accumulator layout gives a lane 4 consecutive columns of ONE row, so a
 // direct store would touch 32 rows per instruction.  Each wave instead passes its accumulators
-// through a private 4 KB LDS buffer, 16 rows at a time (16-byte columns XOR-swizzled by the row:
-// conflict-free for the column-wise writes and the row-wise reads), and then handles rows of 64
-// consecutive columns with 16 lanes x 16 bytes each.
+// through a private 4 KB LDS buffer (XOR-swizzled, conflict-free for the column-wise writes and
+// the row-wise reads) and stores whole row segments of its 64 columns:
+//   - bf16 outputs of a full tile: bias / GELU in the accumulator layout, rounded, 32 rows per pass;
+//   - everything else: fp32 through LDS, 16 rows per pass, then bias / gate / addend per row.
 //
 // A wave's loads and stores retire through one in-order counter, so a load issued behind a
-// store waits for that store's write acknowledgement.  The pass loop therefore contains no
+// store waits for that store's write acknowledgement.  The pass loops therefore contain no
 // load that depends on a recent store: bias and per-sample constants (gate vector, output
 // offset) are fetched once before the first store, and the per-row addend (residual stream,
 // position embedding) is fetched ADDEND_AHEAD passes ahead of its use.
