@@ -101,6 +101,35 @@ def test_branching_factor_one_is_the_flat_rollout(lib):
     assert np.array_equal(z[0], z[wl["T"] + 1])                 # same noise group: same z_0
 
 
+@pytest.mark.parametrize("K,splits", [(3, (1, 4)), (4, (0, 5)), (5, (2,))])
+def test_larger_branching_factors_end_to_end(lib, K, splits):
+    """Larger trees of the scaling study: K = 3, 4 (fused kernel) and 5 (generic kernel)."""
+    wl = synth.WORKLOADS["tiny"]
+    C = 2
+    r = _run_rollout(wl, C, 31, [0, 0], K=K, splits=splits, logp_mean=True)
+    t, cfg, W, cond, sched, D = r["t"], r["cfg"], r["W"], r["cond"], r["sched"], r["D"]
+    o = tree.tree_build(wl["T"], splits, K)
+    assert t.n_leaves == K ** len(splits)
+    vel = lambda zz, tt, ci: dit.forward(cfg, W, zz, tt, cond, ci)
+    zr, lpr, _ = rollout.tree_rollout(o, vel, sched, 31, [0, 0], D, C)
+    z, lp = host(r["z"]), host(r["logp"])
+    assert np.abs(z - zr).max() < 2e-4
+    nz = lpr != 0
+    assert np.all(np.abs(lp[nz] - lpr[nz]) <= 1e-3 * np.abs(lpr[nz])) and np.all(lp[~nz] == 0)
+    # fusion, advantages and Parent-Top1 pruning on the same tree
+    rew = np.tanh(zr[[c * t.n_nodes + t.off[t.T] + l for c in range(C) for l in range(t.n_leaves)]].mean(axis=1) * 30)
+    rew = rew.astype(np.float32)
+    rbar, adv = torch.empty(C * t.n_nodes, device=DEV), torch.empty(C * t.n_nodes, device=DEV)
+    br.fuse_advantage(t, dev(rew), r["logp"], 1.0, 1e-8, 0, synth.ADV_CLIP, rbar, adv)
+    rb_ref = fusion.fuse_rewards(o, rew, lp, 1.0, C)
+    adv_ref = fusion.depth_advantages(o, rb_ref, C, 1e-8, 0, synth.ADV_CLIP)
+    assert np.abs(host(adv) - adv_ref).max() <= 1e-5
+    kept = torch.empty(C * t.n_edges, dtype=torch.int32, device=DEV)
+    nk = torch.zeros(1, dtype=torch.int32, device=DEV)
+    br.prune(t, dev(rew), br.PRUNE_PARENT_TOP1, 0, None, kept, nk)
+    assert np.array_equal(host(kept)[:int(host(nk)[0])], prune.kept_edges(o, rew, C, 1, 0, np.zeros(t.T, np.uint8)))
+
+
 def test_siblings_share_their_prefix_and_chunking_changes_nothing(lib):
     wl = synth.WORKLOADS["tiny"]
     a = _run_rollout(wl, 2, 9, [0, 1])
