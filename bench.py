@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="image", choices=["image", "tiny", "image_large", "video"],
                     help="image is the workload of the headline metric; the others are extra shapes")
+    ap.add_argument("--splits", default=None, help="comma-separated split steps replacing the workload's (extra shapes: "
+                    "the paper's Dense 0,3,6,9 / Mixed 0,4,8,12 / Sparse 0,5,10,15 presets, five splits, ...)")
+    ap.add_argument("--branch", type=int, default=None, help="branching factor K replacing the workload's (3 -> 81, 4 -> 256 leaves)")
+    ap.add_argument("--prompts", type=int, default=None, help="number of prompts (independent trees) replacing the workload's")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time single launches in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
@@ -101,7 +105,13 @@ def main():
         sys.exit("bench.py: no GPU visible")
     br.load()
     dev = "cuda"
-    wl = synth.WORKLOADS[args.workload]
+    wl = dict(synth.WORKLOADS[args.workload])
+    if args.splits is not None:
+        wl["splits"] = tuple(int(x) for x in args.splits.split(",") if x != "")
+    if args.branch is not None:
+        wl["K"] = args.branch
+    if args.prompts is not None:
+        wl["n_cond"] = args.prompts
     cfg, T, C = wl["model"], wl["T"], wl["n_cond"]
     sz = synth.model_sizes(cfg)
     D, L, H, NB = sz["D"], sz["L"], cfg["hidden"], cfg["n_blocks"]
