@@ -134,3 +134,35 @@ def test_fusion_ess_matches_oracle(lib, T, splits, K, C):
         br.fusion_ess(t, dev(logp), beta, ess)
         ref = fusion.ess(o, logp, beta, C)
         assert np.all(np.abs(host(ess) - ref) <= 1e-5 * ref), beta
+
+
+def test_tree_kernels_at_and_beyond_their_largest_trees(lib):
+    """4096 leaves per tree is the most fusion and ESS take, 8191 the most pruning takes; beyond that the
+    calls refuse with a shape error before anything is launched."""
+    T = 12
+    t, o = br.Tree(T, tuple(range(12)), 2, n_tree=1), tree.tree_build(T, tuple(range(12)), 2)
+    assert t.n_leaves == 4096 and t.n_nodes == 8191
+    rng = np.random.default_rng(12)
+    r = rng.standard_normal(t.n_leaves).astype(np.float32)
+    lp = (rng.standard_normal(t.n_nodes) * 0.5).astype(np.float32)
+    rb, adv = _fuse(t, r, lp, 1.0)
+    rb_ref = fusion.fuse_rewards(o, r, lp, 1.0, 1)
+    assert np.abs(rb - rb_ref).max() < 1e-6
+    assert np.abs(adv - fusion.depth_advantages(o, rb_ref, 1, eps=1e-8, ddof=0, a_max=5.0)).max() <= 1e-5
+    ess = torch.empty(t.n_nodes, device=DEV)
+    br.fusion_ess(t, dev(lp), 1.0, ess)
+    ref = fusion.ess(o, lp, 1.0, 1)
+    assert np.all(np.abs(host(ess) - ref) <= 1e-5 * ref)
+    kept = torch.empty(t.n_edges, dtype=torch.int32, device=DEV)
+    nk = torch.zeros(1, dtype=torch.int32, device=DEV)
+    br.prune(t, dev(r), br.PRUNE_EXTREME, 100, None, kept, nk)
+    assert np.array_equal(host(kept)[:int(host(nk)[0])], prune.kept_edges(o, r, 1, 2, 100, np.zeros(T, np.uint8)))
+    big = br.Tree(13, tuple(range(13)), 2, n_tree=1)          # 8192 leaves
+    r2, lp2 = dev(np.zeros(big.n_leaves, np.float32)), dev(np.zeros(big.n_nodes, np.float32))
+    out = torch.empty(big.n_nodes, device=DEV)
+    for call in (lambda: br.fuse_advantage(big, r2, lp2, 1.0, 1e-8, 0, 5.0, out, out.clone()),
+                 lambda: br.fusion_ess(big, lp2, 1.0, out),
+                 lambda: br.prune(big, r2, br.PRUNE_NONE, 0, None, torch.empty(big.n_edges, dtype=torch.int32, device=DEV), nk)):
+        with pytest.raises(br.BranchRolloutError) as e:
+            call()
+        assert e.value.code == -3
