@@ -24,9 +24,8 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
-# per-file extras: keep the attention kernel's MFMA results in VGPRs (its softmax works on them
-# with ordinary vector instructions; accumulation registers would cost a copy per element)
-EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+# per-file extra flags
+EXTRA = {}
 
 
 def _compile(src, obj):

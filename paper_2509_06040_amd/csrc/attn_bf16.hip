@@ -1,13 +1,20 @@
 // bf16 flash attention on the gfx950 matrix cores: softmax(Q K^T / sqrt(d)) V over
 // all L tokens of a sample, one workgroup per (128 queries, head, sample), four
-// wavefronts of 32 queries each, key/value tiles of 64 staged through LDS.
+// wavefronts of 32 queries each, key/value tiles of 64 keys in LDS.
 //
 // Scores are computed transposed, S^T = K Q^T: in the 32x32 MFMA accumulator a
 // lane then holds 16 keys of ONE query (the other 16 sit in lane ^ 32), so the
 // running max / sum / rescale of the online softmax are per-lane scalars and the
 // exponentiated tile is already laid out as the column operand of O^T = V^T P^T.
-// The contraction order of that product is permuted to match the accumulator
-// layout; V is staged transposed ([d][key]) so the row operand is two 8-byte reads.
+// The contraction order of that product is permuted to match the accumulator layout.
+//
+// Both tiles travel from global memory straight into LDS (no registers, no vector
+// instructions on the way), row-major as they lie in the QKV buffer, with their 16-byte
+// chunks permuted per row so that fragment reads spread over the banks.  The row operand
+// of the second product needs V transposed; the LDS transpose read delivers that: in a
+// group of 16 lanes, lane 4 r + q supplies the address of 8 bytes (4 values of row r) and
+// lane j receives element j of rows 0..3, so each lane ends up with four consecutive keys
+// of its own channel.
 #include "common.h"
 #include "dit.h"
 #include "prof.h"
@@ -16,28 +23,46 @@ namespace br {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+#define BR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
 
 constexpr int KV_TILE = 64;
-constexpr int VT_STRIDE = 68;  // bf16 elements per row of the transposed V tile (136 B)
 
+// (a uniform address; saying so keeps it in scalar registers)
+static __device__ inline const char* uniform_ptr(const char* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const char*>(((unsigned long long)hi << 32) | lo);
+}
+
+// slot permutation of the V tile: 16-byte chunk c of row r sits in slot c ^ v_swz(r)
+__device__ inline int v_swz(int r) { return ((r & 1) << 2) | ((r >> 1) & 3); }
+
+// Two waves per SIMD at least: with at most 256 registers a wave the compiler keeps the MFMA
+// results in ordinary vector registers, where the softmax works on them directly
+// (accumulation registers would cost a copy per element).
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
-                                                        int H, int NH, int n_pairs, int grouped, float scale_log2) {
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
+                                                           int H, int NH, int n_pairs, int grouped, float scale_log2) {
   constexpr int CH = DH / 8;    // 16-byte chunks per K row
   constexpr int KS = DH / 16;   // MFMA k-steps of the score product
   constexpr int DB = DH / 32;   // 32-row blocks of O^T
-  constexpr int NKC = KV_TILE * CH / 256;  // K chunks per thread and tile
-  constexpr int NVP = 32 * CH / 256;       // V key-pair items per thread and tile
-  __shared__ __attribute__((aligned(16))) u32x4 sK[2][KV_TILE * CH];
-  __shared__ __attribute__((aligned(16))) bf16 sVt[2][DH * VT_STRIDE];
+  constexpr int RPI = 64 / CH;              // rows covered by one 1 KB load
+  constexpr int LPW = KV_TILE / RPI / 4;    // loads per wave, tile and operand
+  constexpr int NPAR = RPI == 8 ? 1 : 2;    // distinct (row & 7) patterns among a wave's loads
+  constexpr int ROW_B = CH * 16;            // bytes per row
+  constexpr int TILE_B = KV_TILE * ROW_B;
+  __shared__ __attribute__((aligned(1024))) char sK[2][TILE_B];
+  __shared__ __attribute__((aligned(1024))) char sV[2][TILE_B];
 
   // Workgroups are dispatched round-robin over the 8 XCDs.  All query tiles of one
   // (sample, head) read the same keys and values, so they are given to one XCD and run
   // back to back there: K/V then come out of that XCD's L2 instead of being fetched 8 times.
-  const int nq = (L + 127) / 128;
   // (With few pairs that would leave XCDs idle: then tiles are simply dealt out in order.)
+  const int nq = (L + 127) / 128;
   int pair, qt;
   if (grouped) {
     const int x = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -49,7 +74,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   }
   if (pair >= n_pairs) return;
   const int b = pair / NH, h = pair - b * NH;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const size_t ld = (size_t)3 * H;
   const bf16* base = qkv + (size_t)b * L * ld + (size_t)h * DH;
   const int qi = qt * 128 + wv * 32 + l32;
@@ -66,85 +92,78 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   const bf16x2 one2 = {(bf16)1.0f, (bf16)1.0f};
 
-  // The next key/value tile is fetched into registers while the current one is multiplied
-  // out of LDS; two LDS buffers, one barrier per tile.
-  u32x4 rk[NKC];
-  bf16x8 rva[NVP], rvb[NVP];
-  // byte offsets of this thread's items from the first key of a tile; a tile's base address is
-  // uniform, so a fetch is a scalar base plus these 32-bit offsets
+  // Key and value tiles go from global memory straight into LDS, 1 KB (RPI rows) per
+  // instruction: lane i fills bytes 16 i .. 16 i + 15 of the instruction's span, so the chunk
+  // permutation is applied on the global side.
   const unsigned ldb = (unsigned)(ld * 2);
-  unsigned koff[NKC], voff[NVP];
+  const int lrow = lane / CH, slot = lane % CH;
+  unsigned koff[NPAR], voff[NPAR];
 #pragma unroll
-  for (int i = 0; i < NKC; ++i) {
-    const int id = tid + i * 256, row = id / CH, c = id % CH;
-    koff[i] = row * ldb + (H + c * 8) * 2;
+  for (int par = 0; par < NPAR; ++par) {
+    const int r7 = ((RPI * par) & 7) + lrow;
+    koff[par] = lrow * ldb + (H + (slot ^ r7) * 8) * 2;
+    voff[par] = lrow * ldb + (2 * H + (slot ^ v_swz(r7)) * 8) * 2;
   }
-#pragma unroll
-  for (int i = 0; i < NVP; ++i) {
-    const int id = tid + i * 256, p = id & 31, c = id >> 5;
-    voff[i] = 2 * p * ldb + (2 * H + c * 8) * 2;
-  }
-  auto fetch = [&](int k0) {
-    const char* tile = reinterpret_cast<const char*>(base) + (size_t)k0 * ldb;
+  auto issue = [&](int k0, int buf) {
+    const unsigned kdst = (unsigned)(uintptr_t)BR_LPTR(sK[buf]) + wv * LPW * 1024;
+    const unsigned vdst = (unsigned)(uintptr_t)BR_LPTR(sV[buf]) + wv * LPW * 1024;
     if (k0 + KV_TILE <= L) {
+      const char* blk = uniform_ptr(reinterpret_cast<const char*>(base) + (size_t)(k0 + wv * LPW * RPI) * ldb);
 #pragma unroll
-      for (int i = 0; i < NKC; ++i) rk[i] = *reinterpret_cast<const u32x4*>(tile + koff[i]);
-#pragma unroll
-      for (int i = 0; i < NVP; ++i) {
-        rva[i] = *reinterpret_cast<const bf16x8*>(tile + voff[i]);
-        rvb[i] = *reinterpret_cast<const bf16x8*>(tile + voff[i] + ldb);
-      }
-    } else {  // ragged last tile: keys past the end read the last key (their scores are masked)
-      const int last = L - 1 - k0;
-#pragma unroll
-      for (int i = 0; i < NKC; ++i) {
-        const int id = tid + i * 256, row = id / CH, c = id % CH;
-        rk[i] = *reinterpret_cast<const u32x4*>(tile + min(row, last) * ldb + (H + c * 8) * 2);
+      for (int t = 0; t < LPW; ++t) {
+        const char* src = blk + (size_t)t * RPI * ldb;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kdst + t * 1024), "v"(koff[t % NPAR]), "s"(src) : "memory", "m0");
       }
 #pragma unroll
-      for (int i = 0; i < NVP; ++i) {
-        const int id = tid + i * 256, p = id & 31, c = id >> 5;
-        rva[i] = *reinterpret_cast<const bf16x8*>(tile + min(2 * p, last) * ldb + (2 * H + c * 8) * 2);
-        rvb[i] = *reinterpret_cast<const bf16x8*>(tile + min(2 * p + 1, last) * ldb + (2 * H + c * 8) * 2);
+      for (int t = 0; t < LPW; ++t) {
+        const char* src = blk + (size_t)t * RPI * ldb;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vdst + t * 1024), "v"(voff[t % NPAR]), "s"(src) : "memory", "m0");
       }
-    }
-  };
-  auto stash = [&](int buf) {
-    // K tile: row-major, chunk c of row r in slot c ^ (r & 7)
+    } else {  // ragged last tile: rows past the end read the last key (their scores are masked)
+      const char* blk = uniform_ptr(reinterpret_cast<const char*>(base));
 #pragma unroll
-    for (int i = 0; i < NKC; ++i) {
-      const int id = tid + i * 256, row = id / CH, c = id % CH;
-      sK[buf][row * CH + (c ^ (row & 7))] = rk[i];
-    }
-    // V tile transposed: a thread holds two neighbouring keys of one 8-wide d chunk and
-    // writes eight (key pair) words
+      for (int t = 0; t < LPW; ++t) {
+        const int row = (wv * LPW + t) * RPI + lrow;
+        const unsigned off = (unsigned)min(k0 + row, L - 1) * ldb + (H + (slot ^ (row & 7)) * 8) * 2;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kdst + t * 1024), "v"(off), "s"(blk) : "memory", "m0");
+      }
 #pragma unroll
-    for (int i = 0; i < NVP; ++i) {
-      const int id = tid + i * 256, p = id & 31, c = id >> 5;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        bf16x2 pr = {rva[i][e], rvb[i][e]};
-        *reinterpret_cast<bf16x2*>(&sVt[buf][(c * 8 + e) * VT_STRIDE + 2 * p]) = pr;
+      for (int t = 0; t < LPW; ++t) {
+        const int row = (wv * LPW + t) * RPI + lrow;
+        const unsigned off = (unsigned)min(k0 + row, L - 1) * ldb + (2 * H + (slot ^ v_swz(row & 7)) * 8) * 2;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vdst + t * 1024), "v"(off), "s"(blk) : "memory", "m0");
       }
     }
   };
 
+  // transposed reads of V: in a group of 16 lanes, lane 4 r + q supplies the 8 bytes at
+  // (key K0 + r, d0 + 4 q .. 4 q + 3) and lane j receives (keys K0 .. K0 + 3, d0 + j)
+  const int jj = lane & 15, g1 = (lane >> 4) & 1;
+  const int vrow = 4 * lh + (jj >> 2);  // row within a group of 8 keys
+  unsigned vaddr[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d) {
+    const int chunk = d * 4 + 2 * g1 + ((jj & 3) >> 1);
+    vaddr[d] = vrow * ROW_B + (chunk ^ v_swz(vrow)) * 16 + 8 * (jj & 1);
+  }
+
+  // Two LDS buffers, one barrier per tile: the next tile is fetched while the current one is
+  // multiplied.  Every iteration issues the same number of fetches (the last one fetches its
+  // own tile again, into the idle buffer), so the wait below is exact.
   const int nkv = (L + KV_TILE - 1) / KV_TILE;
-  fetch(0);
-  stash(0);
+  issue(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  // Pin the query fragments in registers here.  Left alone, the compiler sinks their loads to
-  // just before the loop, and its wait-count bookkeeping at the loop header then makes every
-  // iteration wait for the key/value fetch it has just issued.
+  // Pin the query fragments in registers here; left alone, the compiler sinks their loads
+  // into the loop.
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   for (int it = 0; it < nkv; ++it) {
     const int k0 = it * KV_TILE, buf = it & 1;
-    if (it + 1 < nkv) fetch(k0 + KV_TILE);
+    // the other buffer was last read one tile ago, before the previous barrier
+    issue(min(it + 1, nkv - 1) * KV_TILE, buf ^ 1);
 
     // S^T tile: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query l32
     f32x16 s[2];
@@ -156,7 +175,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int c = ks * 2 + lh;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][row * CH + (c ^ (row & 7))]);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ (row & 7))) * 16]);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
       }
     }
@@ -196,6 +215,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
     }
 
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
+    const char __attribute__((address_space(3)))* vt = (const char __attribute__((address_space(3)))*)BR_LPTR(sV[buf]);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -209,18 +229,19 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
           const bf16x2 pr = {pf[e], pf[e + 1]};
           l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_run, false);
         }
-        const int kofs = kb * 32 + j * 16 + lh * 4;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          const bf16* vr = &sVt[buf][(d * 32 + l32) * VT_STRIDE + kofs];
-          const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vr);
-          const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vr + 8);
-          const bf16x8 vf = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+          const auto* p0 = vt + vaddr[d] + (kb * 32 + j * 16) * ROW_B;
+          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * ROW_B));
+          union { s16x4 s[2]; bf16x8 v; } u;
+          u.s[0] = v0;
+          u.s[1] = v1;
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf, o[d], 0, 0, 0);
         }
       }
-    // the other buffer was last read one tile ago, before the previous barrier
-    if (it + 1 < nkv) stash(buf ^ 1);
+    // the next tile has landed in this wave's share of the other buffer; after the barrier, in all of it
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
@@ -238,6 +259,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
       }
   }
 }
+
 
 br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st) {
   BR_REQUIRE(L >= 1, BR_EINVAL, "attention: empty sequence");

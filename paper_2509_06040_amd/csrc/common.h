@@ -39,6 +39,20 @@ struct SampleMap {
   const int* group = nullptr;  // dev or nullptr: modulation group of a sample (default: its condition)
 };
 
+// Streaming stores of four consecutive elements, for data that the writing kernel does not
+// read again: the lines are not kept in the cache of the compute die that wrote them, which
+// leaves that cache to the operands still in use.
+__device__ inline void store4_stream(float* p, float a, float b, float c, float d) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  f32x4 v = {a, b, c, d};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+__device__ inline void store4_stream(__bf16* p, float a, float b, float c, float d) {
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+  __builtin_nontemporal_store(v, reinterpret_cast<bf16x4*>(p));
+}
+
 }  // namespace br
 
 struct br_tree {

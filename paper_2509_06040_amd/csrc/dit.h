@@ -180,7 +180,7 @@ struct Epilogue {
       store4<T>(reinterpret_cast<T*>(a.out) + (long long)m * a.ldo + n, gelu_tanh_f(v0), gelu_tanh_f(v1),
                 gelu_tanh_f(v2), gelu_tanh_f(v3));
     } else if (MODE == EPI_BIAS_GATE_RES) {
-      store4<float>(reinterpret_cast<float*>(a.out) + (long long)m * a.ldo + n, fmaf(sc.gate.x, v0, add.x),
+      store4_stream(reinterpret_cast<float*>(a.out) + (long long)m * a.ldo + n, fmaf(sc.gate.x, v0, add.x),
                     fmaf(sc.gate.y, v1, add.y), fmaf(sc.gate.z, v2, add.z), fmaf(sc.gate.w, v3, add.w));
     } else if (MODE == EPI_PATCH_EMBED) {
       store4<float>(reinterpret_cast<float*>(a.out) + sc.o + (long long)tok * a.ldo + n, v0 + add.x, v1 + add.y,

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
     for (int i = 0; i < VPL; ++i) {
       const int c4 = lane + 64 * i;
       const float4 a = sh[c4], g = sc[c4];
-      store4<T>(orow + 4 * c4, fmaf((v[i].x - mean) * rstd, 1.f + g.x, a.x), fmaf((v[i].y - mean) * rstd, 1.f + g.y, a.y),
+      store4_stream(orow + 4 * c4, fmaf((v[i].x - mean) * rstd, 1.f + g.x, a.x), fmaf((v[i].y - mean) * rstd, 1.f + g.y, a.y),
                 fmaf((v[i].z - mean) * rstd, 1.f + g.z, a.z), fmaf((v[i].w - mean) * rstd, 1.f + g.w, a.w));
     }
   } else {

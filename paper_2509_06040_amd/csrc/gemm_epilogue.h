@@ -175,7 +175,7 @@ __device__ inline void wave_epilogue_bf16_full(const f32x16_e (&acc)[TN][TM], ch
     for (int q = 0; q < 4; ++q) {
       const int r = rrow + 8 * q;
       const u32x4_e v = *reinterpret_cast<const u32x4_e*>(ebuf + r * 128 + ((rc ^ ((r >> 1) & 7)) << 4));
-      *reinterpret_cast<u32x4_e*>(obase + (long long)(j * 32 + 8 * q) * epi.a.ldo) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4_e*>(obase + (long long)(j * 32 + 8 * q) * epi.a.ldo));
     }
   }
 }
