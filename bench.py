@@ -37,20 +37,20 @@ TILE_NAMES = {4: "256x256 lds-direct", 5: "128x128 lds-direct",
 # see profiles/hot_kernels_hbm_traffic.md.  Valid only for the kernel sources hashed below.
 TRAFFIC = {
     "gemm_bf16[bias_gate_residual,256x256 persistent stream]": dict(
-        bytes_per_launch=283315.62 * 1024 * 2.0 + 177334.40 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="aa24df171a1ccc2d7d9569d9c047141da9ec4b5d"),
+        bytes_per_launch=278983.45 * 1024 * 2.0 + 177343.03 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
     "gemm_bf16[bias_gelu,256x256 persistent stream]": dict(
-        bytes_per_launch=383501.76 * 1024 * 2.0 + 309670.74 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="aa24df171a1ccc2d7d9569d9c047141da9ec4b5d"),
+        bytes_per_launch=237541.44 * 1024 * 2.0 + 309722.11 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
     "gemm_bf16[bias,256x256 persistent stream]": dict(
-        bytes_per_launch=262797.57 * 1024 * 2.0 + 189372.00 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h'), sha1="aa24df171a1ccc2d7d9569d9c047141da9ec4b5d"),
+        bytes_per_launch=151446.25 * 1024 * 2.0 + 189520.07 * 1024 * 1.0,
+        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
     "attn_bf16[d64]": dict(
-        bytes_per_launch=94801.99 * 1024 * 2.0 + 63124.00 * 1024 * 1.0,
-        sources=('attn_bf16.hip',), sha1="326b4d101e6726f9589016066504c0c1355e2dd3"),
+        bytes_per_launch=94771.06 * 1024 * 2.0 + 63124.01 * 1024 * 1.0,
+        sources=('attn_bf16.hip',), sha1="5c4075891ea03d7abea6e1c84648790ee6f2974a"),
     "ln_modulate": dict(
-        bytes_per_launch=63168.13 * 1024 * 2.0 + 62947.41 * 1024 * 1.0,
-        sources=('dit_kernels.hip',), sha1="6169a0553b7a182216bf177b290d38a6ac4052ed"),
+        bytes_per_launch=63167.22 * 1024 * 2.0 + 62947.45 * 1024 * 1.0,
+        sources=('dit_kernels.hip', 'common.h'), sha1="fe54c511428b8d901e03fa5064dd54b2441efca3"),
 }
 
 
