@@ -263,6 +263,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
 
 br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st) {
   BR_REQUIRE(L >= 1, BR_EINVAL, "attention: empty sequence");
+  // the ragged last tile addresses its rows with 32-bit byte offsets from the sample's first row
+  BR_REQUIRE((unsigned long long)L * 3ull * NH * DH * 2ull < (1ull << 32), BR_ESHAPE,
+             "attention: one sample's QKV rows exceed 4 GiB");
   const long long n_pairs = (long long)B * NH;
   const int grouped = n_pairs >= 32 ? 1 : 0;
   const long long n_blocks = (grouped ? (n_pairs + 7) / 8 * 8 : n_pairs) * cdiv(L, 128);

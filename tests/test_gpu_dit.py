@@ -84,8 +84,11 @@ def test_attention_fp32(lib, dh, nh, L, B):
     assert rel_l2(host(out), _attention_ref(qkv.astype(np.float64), nh)) < 2e-6
 
 
+# the last four: enough (sample, head) pairs for the XCD-grouped tile order, with ragged query
+# and key tiles, one key tile only, and the last sample ending at the end of the buffer
 @pytest.mark.parametrize("dh,nh,L,B", [(64, 2, 1, 1), (64, 3, 77, 2), (64, 2, 1101, 1), (128, 2, 130, 2), (128, 1, 640, 1),
-                                        (64, 1, 128, 1)])
+                                        (64, 1, 128, 1), (64, 16, 203, 3), (128, 8, 150, 5), (64, 12, 63, 3),
+                                        (128, 9, 257, 4)])
 def test_attention_bf16(lib, dh, nh, L, B):
     rng = np.random.default_rng(dh + L)
     qkv = _bf(rng.standard_normal((B, L, 3 * nh * dh)).astype(np.float32) * 1.5)
