@@ -96,7 +96,7 @@ def test_attention_bf16(lib, dh, nh, L, B):
     br.op_attention(br.BF16, dev(qkv, torch.bfloat16), out, nh)
     ref = _attention_ref(qkv.astype(np.float64), nh)
     err = rel_l2(host(out), ref)
-    assert err < 6e-3, err                       # bf16 probabilities and output rounding
+    assert err < 3e-3, err                       # bf16 probabilities and output rounding (measured 1.8e-3)
 
 
 @pytest.mark.parametrize("dt", [br.F32, br.BF16])
