@@ -29,7 +29,8 @@ br_status br_op_gemm(int32_t dtype, int32_t epilogue, const void* A, int32_t lda
                      const int32_t* cond, int32_t L, int32_t variant, void* stream);
 
 /* out[b, l, h*DH + d] = softmax_j(q_l . k_j / sqrt(DH)) v_j for every sample b and
- * head h; qkv dev [B, L, 3*NH*DH] (q | k | v), out dev [B, L, NH*DH], both `dtype`. */
+ * head h; qkv dev [B, L, 3*NH*DH] (q | k | v), out dev [B, L, NH*DH], both `dtype`.
+ * BR_BF16: DH 64 or 128, qkv 16-byte aligned, L*3*NH*DH*2 below 4 GiB (BR_ESHAPE otherwise). */
 br_status br_op_attention(int32_t dtype, const void* qkv, void* out, int32_t B, int32_t L,
                           int32_t NH, int32_t DH, void* stream);
 
