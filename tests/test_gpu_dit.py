@@ -99,6 +99,18 @@ def test_attention_bf16(lib, dh, nh, L, B):
     assert err < 3e-3, err                       # bf16 probabilities and output rounding (measured 1.8e-3)
 
 
+def test_attention_bf16_rejects_what_it_cannot_address(lib):
+    import ctypes as C
+    raw = br.load()
+    buf = torch.zeros(64, dtype=torch.bfloat16, device=DEV)
+    p = C.c_void_p(buf.data_ptr())
+    # rows of one sample beyond 4 GiB (the check precedes any launch; the buffers are never touched)
+    assert raw.br_op_attention(br.BF16, p, p, 1, 400000, 16, 128, None) == -3
+    assert b"4 GiB" in raw.br_last_error()
+    assert raw.br_op_attention(br.BF16, p, p, 1, 16, 2, 32, None) == -3          # head dim 32 in bf16
+    assert raw.br_op_attention(br.BF16, p, p, 1, 0, 2, 64, None) == -1
+
+
 @pytest.mark.parametrize("dt", [br.F32, br.BF16])
 def test_ln_modulate(lib, dt):
     rng = np.random.default_rng(1)
