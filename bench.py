@@ -37,19 +37,19 @@ TILE_NAMES = {4: "256x256 lds-direct", 5: "128x128 lds-direct",
 # see profiles/hot_kernels_hbm_traffic.md.  Valid only for the kernel sources hashed below.
 TRAFFIC = {
     "gemm_bf16[bias_gate_residual,256x256 persistent stream]": dict(
-        bytes_per_launch=279191.31 * 1024 * 2.0 + 177344.45 * 1024 * 1.0,
+        bytes_per_launch=279020.25 * 1024 * 2.0 + 177344.78 * 1024 * 1.0,
         sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
     "gemm_bf16[bias_gelu,256x256 persistent stream]": dict(
-        bytes_per_launch=237445.93 * 1024 * 2.0 + 309799.20 * 1024 * 1.0,
+        bytes_per_launch=237943.44 * 1024 * 2.0 + 309737.46 * 1024 * 1.0,
         sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
     "gemm_bf16[bias,256x256 persistent stream]": dict(
-        bytes_per_launch=150814.49 * 1024 * 2.0 + 189527.75 * 1024 * 1.0,
+        bytes_per_launch=151099.73 * 1024 * 2.0 + 189502.07 * 1024 * 1.0,
         sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
     "attn_bf16[d64]": dict(
-        bytes_per_launch=94769.97 * 1024 * 2.0 + 63124.01 * 1024 * 1.0,
-        sources=('attn_bf16.hip',), sha1="7911295e2869778a0595081e1887e25649aec590"),
+        bytes_per_launch=94775.25 * 1024 * 2.0 + 63124.00 * 1024 * 1.0,
+        sources=('attn_bf16.hip',), sha1="fbe6a1e9f145fb7c60c7fe2334196b71d35a5efc"),
     "ln_modulate": dict(
-        bytes_per_launch=63167.21 * 1024 * 2.0 + 62947.46 * 1024 * 1.0,
+        bytes_per_launch=63167.22 * 1024 * 2.0 + 62947.46 * 1024 * 1.0,
         sources=('dit_kernels.hip', 'common.h'), sha1="fe54c511428b8d901e03fa5064dd54b2441efca3"),
 }
 

@@ -15,6 +15,8 @@
 // group of 16 lanes, lane 4 r + q supplies the address of 8 bytes (4 values of row r) and
 // lane j receives element j of rows 0..3, so each lane ends up with four consecutive keys
 // of its own channel.
+#include <type_traits>
+
 #include "common.h"
 #include "dit.h"
 #include "prof.h"
@@ -41,11 +43,11 @@ static __device__ inline const char* uniform_ptr(const char* p) {
 // slot permutation of the V tile: 16-byte chunk c of row r sits in slot c ^ v_swz(r)
 __device__ inline int v_swz(int r) { return ((r & 1) << 2) | ((r >> 1) & 3); }
 
-// Two waves per SIMD at least: with at most 256 registers a wave the compiler keeps the MFMA
-// results in ordinary vector registers, where the softmax works on them directly
-// (accumulation registers would cost a copy per element).
+// With at most 256 registers a wave (two waves per SIMD) the compiler keeps the MFMA results in
+// ordinary vector registers, where the softmax works on them directly (accumulation registers
+// would cost a copy per element).  Head dim 64 fits in 128 registers: four waves per SIMD.
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
+__global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
                                                            int H, int NH, int n_pairs, int grouped, float scale_log2) {
   constexpr int CH = DH / 8;    // 16-byte chunks per K row
   constexpr int KS = DH / 16;   // MFMA k-steps of the score product
@@ -80,6 +82,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
   const bf16* base = qkv + (size_t)b * L * ld + (size_t)h * DH;
   const int qi = qt * 128 + wv * 32 + l32;
   const int qc = min(qi, L - 1);
+  const bool active = qt * 128 + wv * 32 < L;  // (uniform over the wave)
 
   bf16x8 qf[KS];
 #pragma unroll
@@ -160,7 +163,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
   // into the loop.
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
-  for (int it = 0; it < nkv; ++it) {
+  // One key tile.  NKB: 32-key blocks of the tile that hold any key at all (2, or 1 in a short
+  // last tile); MASK: the tile runs past the end of the sequence.  Only the last tile of a
+  // ragged sequence is compiled with masking, so the loop over full tiles carries none of it.
+  auto tile = [&](int it, auto NKBc, auto MASKc) {
+    constexpr int NKB = decltype(NKBc)::value;
+    constexpr bool MASK = decltype(MASKc)::value;
     const int k0 = it * KV_TILE, buf = it & 1;
     // the other buffer was last read one tile ago, before the previous barrier
     issue(min(it + 1, nkv - 1) * KV_TILE, buf ^ 1);
@@ -168,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
     // S^T tile: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query l32
     f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
       const int row = kb * 32 + l32;
@@ -179,10 +187,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
       }
     }
-    // keys past the end exist only in the last tile of a ragged sequence
-    if (k0 + KV_TILE > L) {
+    if (MASK) {  // keys past the end
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
@@ -193,14 +200,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
     // into the exponent: p = exp2(s c - m c)
     float mx = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
     const float mc = m_new * scale_log2;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
     // the accumulators are rescaled only when some query of this wave saw a new maximum
@@ -217,7 +224,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
     const char __attribute__((address_space(3)))* vt = (const char __attribute__((address_space(3)))*)BR_LPTR(sV[buf]);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         bf16x8 pf;
@@ -243,8 +250,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const bf16* __restric
     // the next tile has landed in this wave's share of the other buffer; after the barrier, in all of it
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+  };
+  using K1 = std::integral_constant<int, 1>;
+  using K2 = std::integral_constant<int, 2>;
+  const int nfull = L / KV_TILE;
+  if (active) {
+    for (int it = 0; it < nfull; ++it) tile(it, K2{}, std::false_type{});
+    if (nfull < nkv) {
+      if (L - nfull * KV_TILE <= 32) tile(nfull, K1{}, std::true_type{});
+      else tile(nfull, K2{}, std::true_type{});
+    }
+  } else {
+    // a wave whose 32 queries all lie past the end only keeps up its share of the tile traffic
+    for (int it = 0; it < nkv; ++it) {
+      issue(min(it + 1, nkv - 1) * KV_TILE, (it & 1) ^ 1);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
   }
-
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_tot;
   if (qi < L) {
