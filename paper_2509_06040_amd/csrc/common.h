@@ -27,6 +27,9 @@ br_status fail(br_status code, const std::string& msg);
 
 #define BR_LAUNCH_CHECK() BR_HIP(hipGetLastError())
 
+// Compute units of the current device (cached per device; 256 if the query fails).
+int device_cu_count();
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 

@@ -224,12 +224,12 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
                               int variant, hipStream_t st) {
   int tile, group_n = 0;
   if (variant < 0) {
-    // Measured on MI355X (256 compute units).  With r = (256x256 tiles) / (compute units):
+    // Measured on MI355X.  With r = (256x256 tiles) / (compute units):
     // up to half a round of tiles, 256x128 tiles put twice as many units to work; up to one
     // round the persistent 256x256 kernel is best; beyond that it stays best unless the last
     // round would be mostly empty (r = 1.08 costs two rounds), where 128x128 tiles win.
     const long long t256 = (long long)cdiv(M, 256) * cdiv(N, 256);
-    const double r = (double)t256 / 256.0;
+    const double r = (double)t256 / (double)device_cu_count();
     const bool stream_ok = gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2);
     if (r <= 0.5)
       tile = 6;

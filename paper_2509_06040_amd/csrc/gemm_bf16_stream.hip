@@ -269,13 +269,7 @@ static br_status stream_launch(const bf16* A, int lda, const bf16* W, int ldw, i
   // panels x 4 column panels, the squarest footprint, i.e. the fewest operand panels to pull
   // into its L2 per round (a third fewer fetched bytes than whole rows of 12 or 16 tiles).
   if (group_n <= 0 || group_n > tiles_n) group_n = tiles_n > 4 ? 4 : tiles_n;
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0;
-    BR_HIP(hipGetDevice(&dev));
-    BR_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    if (n_cu <= 0) n_cu = 256;
-  }
+  const int n_cu = device_cu_count();
   const int nt = tiles_m * tiles_n;
   const int grid = nt < n_cu ? nt : n_cu;
   hipLaunchKernelGGL((gemm_bf16_stream_kernel<MODE, TOUT>), dim3(grid), dim3(512), 0, st, A, lda, W, ldw, M, N, K,

@@ -12,17 +12,21 @@ struct StepCoef {
   int noise;        // 0: deterministic step, no log-prob
   double c0;        // -D ln std - D/2 ln 2 pi
   double inv_div;   // 1 or 1/D
-  double inv_2var;  // 1/(2 std^2)
+  float inv_std;    // 1/std (0 on a deterministic step)
 };
 StepCoef step_coef(const br_sched* s, int i, long long D);
-int sde_nblk(long long D);
 br_status launch_root_noise(const br_tree* t, uint64_t seed, const int* noise_group, long long D, float* z,
                             hipStream_t st);
+// `scratch` of the two launchers below: sde_scratch_floats(n_items, D) floats = one 64-bit word per child
+// / edge of a launch (at most n_items), 8-byte aligned; the words must be zero (launch_sde_scratch_reset)
+// before the first launch and are left at zero by every launch.
+size_t sde_scratch_floats(long long n_items, long long D);
+br_status launch_sde_scratch_reset(float* scratch, long long n_items, long long D, hipStream_t st);
 br_status launch_sde_step(const br_tree* t, const br_sched* s, uint64_t seed, int i, long long D, const float* v,
-                          int v_compact, float* z, float* logp, float* partials, hipStream_t st);
+                          int v_compact, float* z, float* logp, float* scratch, hipStream_t st);
 br_status launch_logp_eval(const br_sched* s, int i, long long D, const float* z, const float* v, const int* crow,
-                           const int* prow, const int* vrow, const int* out_slot, int n_edges, float* logp_out,
-                           float* partials, hipStream_t st);
+                           const int* prow, const int* vrow, const int* out_slot, int n_edges, long long n_items,
+                           float* logp_out, float* scratch, hipStream_t st);
 br_status launch_fill_zero(float* p, long long n, hipStream_t st);
 br_status launch_noise_stream(uint64_t seed, uint32_t node, uint32_t step, uint32_t tag, long long nq, uint32_t* words,
                               float* normals, hipStream_t st);

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <new>
+#include <mutex>
 #include <numeric>
 
 #include "common.h"
@@ -22,7 +23,23 @@ void philox_host(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t 
   philox4x32_10(k, c0, c1, c2, c3, out);
 }
 
+int device_cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 br_status tree_device(const br_tree* t, TreeDev* out) {
+  // one mirror per tree, created by br_tree_upload or by the first call that needs it; the
+  // lock makes that first call safe when several threads share one tree
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
   int dev = 0;
   BR_HIP(hipGetDevice(&dev));
   const size_t nn = (size_t)t->n_nodes, noff = (size_t)t->T + 2;
@@ -36,7 +53,8 @@ br_status tree_device(const br_tree* t, TreeDev* out) {
     const std::vector<int>* arrs[6] = {&t->parent, &t->depth, &t->leaf_lo, &t->leaf_hi, &t->first_child, &t->n_child};
     for (int a = 0; a < 6; ++a) std::copy(arrs[a]->begin(), arrs[a]->end(), h.begin() + noff + a * nn);
     int* d = nullptr;
-    BR_HIP(hipMalloc((void**)&d, h.size() * sizeof(int)));
+    if (hipMalloc((void**)&d, h.size() * sizeof(int)) != hipSuccess || !d)
+      return fail(BR_ENOMEM, "tree: device allocation of the topology arrays failed");
     hipError_t e = hipMemcpy(d, h.data(), h.size() * sizeof(int), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       (void)hipFree(d);
@@ -150,6 +168,12 @@ extern "C" br_status br_tree_info(const br_tree* t, int32_t* n_nodes, int32_t* n
   if (leaf_lo) *leaf_lo = t->leaf_lo.data();
   if (leaf_hi) *leaf_hi = t->leaf_hi.data();
   return BR_OK;
+}
+
+extern "C" br_status br_tree_upload(const br_tree* t) {
+  BR_REQUIRE(t != nullptr, BR_EINVAL, "br_tree_upload: tree is NULL");
+  TreeDev td;
+  return tree_device(t, &td);
 }
 
 extern "C" void br_tree_free(br_tree* t) {
