@@ -66,6 +66,11 @@ br_status br_tree_info(const br_tree* tree, int32_t* n_nodes, int32_t* n_edges, 
                        int32_t* n_tree, const int32_t** width, const int32_t** off,
                        const int32_t** parent, const int32_t** depth, const int32_t** branch,
                        const int32_t** leaf_lo, const int32_t** leaf_hi);
+/* Copies the topology arrays to the current GPU (a few KB, one blocking copy; BR_ENOMEM /
+ * BR_EDEVICE on failure).  br_fuse_advantage, br_prune and br_fusion_ess need that copy and
+ * make it themselves on their first call for a tree that has none; after br_tree_upload they
+ * only enqueue kernels.  Safe to call again. */
+br_status br_tree_upload(const br_tree* tree);
 void br_tree_free(br_tree* tree);
 
 /* ------------------------------------------------------------------------- *
@@ -264,7 +269,9 @@ br_status br_velocity(const br_model* model, const float* z, float t, const void
 /* One SDE step of the rollout with a caller-given velocity (the fused
  * step/noise/log-prob/expand kernel alone): advances the depth-`step` frontier
  * stored in z_nodes to depth step+1.  v_parents dev [n_tree*width[step], D],
- * row = tree*width[step] + j.  partials dev: scratch of br_sde_scratch_bytes(). */
+ * row = tree*width[step] + j.  scratch dev, 8-byte aligned: br_sde_scratch_bytes() bytes (one 64-bit
+ * word per leaf, in which the blocks working on a child accumulate its log-prob; contents on entry
+ * do not matter). */
 size_t br_sde_scratch_bytes(const br_tree* tree, int64_t D);
 br_status br_sde_step(const br_tree* tree, const br_sched* sched, uint64_t seed, int32_t step,
                       int64_t D, const float* v_parents, float* z_nodes, float* logp_edges,

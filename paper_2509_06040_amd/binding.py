@@ -25,7 +25,7 @@ WEIGHT_ORDER = ("patch_w", "patch_b", "pos", "cond_w", "cond_b", "t1_w", "t1_b",
 _MATRICES = {n for n in WEIGHT_ORDER if n.endswith("_w")}
 
 EXPORTS = (
-    "br_last_error", "br_tree_build", "br_tree_info", "br_tree_free", "br_model_create", "br_model_free",
+    "br_last_error", "br_tree_build", "br_tree_info", "br_tree_upload", "br_tree_free", "br_model_create", "br_model_free",
     "br_workspace_bytes", "br_rollout", "br_logprob", "br_fuse_advantage", "br_prune", "br_reward_scratch_bytes",
     "br_leaf_reward", "br_grpo_objective", "br_velocity", "br_sde_scratch_bytes", "br_sde_step", "br_root_noise",
     "br_noise_stream", "br_depth_mask_window", "br_depth_mask_seeded", "br_mix_schedule", "br_fusion_ess", "br_op_gemm", "br_op_attention",
@@ -106,6 +106,10 @@ class Tree:
         cp = lambda p, n: np.ctypeslib.as_array(p, shape=(n,)).copy()
         self.width, self.off = cp(ptrs[0], T + 1), cp(ptrs[1], T + 2)
         self.parent, self.depth, self.branch, self.leaf_lo, self.leaf_hi = (cp(p, nn.value) for p in ptrs[2:])
+
+    def upload(self):
+        _check(load().br_tree_upload(self._h))
+        return self
 
     def __del__(self):
         if _lib is not None and getattr(self, "_h", None):

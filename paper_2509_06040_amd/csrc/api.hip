@@ -1,7 +1,6 @@
 // C-ABI entry points and the frontier scheduler: per step, all nodes of one depth
-// (over all trees) go through the network as one batch, so shared prefixes are
-// evaluated once (Alg. 1, tree-building loop; Sec. 1 "shared prefixes amortize
-// computation").
+// (over all trees) go through the network as one batch, so a prefix shared by
+// several leaves is evaluated once (Sec. 1; Alg. 1, tree-building loop).
 #include <algorithm>
 #include <cstring>
 #include <cmath>
@@ -45,7 +44,7 @@ Sizes sizes_for(const br_tree* t, const br_model* m, int max_batch) {
   if (t) {
     s.n_cond = t->n_tree;
     s.v_rows = max_frontier(t);
-    s.partial_floats = (long long)t->n_tree * t->n_leaves * sde_nblk(m->D);
+    s.partial_floats = (long long)sde_scratch_floats((long long)t->n_tree * t->n_leaves, m->D);
     s.plan_ints = 9LL * t->n_tree * t->n_nodes + max_batch;
   } else {
     s.n_cond = max_batch;
@@ -93,6 +92,7 @@ extern "C" br_status br_rollout(const br_tree* tree, const br_model* model, cons
   const long long D = model->D;
   if ((s = launch_fill_zero(logp_edges, (long long)tree->n_tree * tree->n_nodes, st)) != BR_OK) return s;
   if ((s = launch_root_noise(tree, seed, noise_group, D, z_nodes, st)) != BR_OK) return s;
+  if ((s = launch_sde_scratch_reset(fb.sde_partials, (long long)tree->n_tree * tree->n_leaves, D, st)) != BR_OK) return s;
   if ((s = embed_cond(model, fb, cond_tokens, tree->n_tree, st)) != BR_OK) return s;
   float* v = v_nodes ? v_nodes : fb.v;
   for (int i = 0; i < tree->T; ++i) {
@@ -119,7 +119,7 @@ extern "C" br_status br_logprob(const br_tree* tree, const br_model* model, cons
   if ((s = check_sched(tree, sched, "br_logprob")) != BR_OK) return s;
   if (n_edges == 0) return BR_OK;
   hipStream_t st = (hipStream_t)stream;
-  const int nn = tree->n_nodes, T = tree->T;
+  const int nn = tree->n_nodes;
   const long long total_nodes = (long long)tree->n_tree * nn;
   BR_REQUIRE(n_edges <= total_nodes, BR_EINVAL, "br_logprob: more edges than the forest has");
   for (int e = 0; e < n_edges; ++e) {
@@ -204,9 +204,11 @@ extern "C" br_status br_logprob(const br_tree* tree, const br_model* model, cons
 
   if ((s = embed_cond(model, fb, cond_tokens, tree->n_tree, st)) != BR_OK) return s;
   const long long D = model->D;
+  if ((s = launch_sde_scratch_reset(fb.sde_partials, (long long)tree->n_tree * tree->n_leaves, D, st)) != BR_OK) return s;
   auto eval_range = [&](int e0, int e1) {  // edges [e0, e1): one step, velocities (if any) in fb.v
     return launch_logp_eval(sched, edges[e0].step, D, z_nodes, fb.v, fb.plan + o_crow + e0, fb.plan + o_prow + e0,
-                            fb.plan + o_vrow + e0, fb.plan + o_slot + e0, e1 - e0, logp_out, fb.sde_partials, st);
+                            fb.plan + o_vrow + e0, fb.plan + o_slot + e0, e1 - e0, (long long)tree->n_tree * tree->n_leaves,
+                            logp_out, fb.sde_partials, st);
   };
   // deterministic steps: no evaluation, log-prob 0
   for (int e0 = 0; e0 < n_edges;) {
@@ -349,7 +351,7 @@ extern "C" br_status br_grpo_objective(const float* logp_new, const float* logp_
 
 extern "C" size_t br_sde_scratch_bytes(const br_tree* tree, int64_t D) {
   if (!tree || D < 4) return 0;
-  return (size_t)tree->n_tree * tree->n_leaves * sde_nblk(D) * sizeof(float);
+  return sde_scratch_floats((long long)tree->n_tree * tree->n_leaves, D) * sizeof(float);
 }
 
 extern "C" br_status br_sde_step(const br_tree* tree, const br_sched* sched, uint64_t seed, int32_t step, int64_t D,
@@ -361,6 +363,9 @@ extern "C" br_status br_sde_step(const br_tree* tree, const br_sched* sched, uin
   BR_REQUIRE(step >= 0 && step < tree->T, BR_EINVAL, "br_sde_step: step outside [0, T)");
   BR_REQUIRE(D >= 4 && D % 4 == 0, BR_ESHAPE, "br_sde_step: D must be a positive multiple of 4");
   BR_REQUIRE(scratch_bytes >= br_sde_scratch_bytes(tree, D), BR_EWORKSPACE, "br_sde_step: scratch too small");
+  BR_REQUIRE(((uintptr_t)scratch & 7) == 0, BR_EINVAL, "br_sde_step: scratch must be 8-byte aligned");
+  if ((s = launch_sde_scratch_reset((float*)scratch, (long long)tree->n_tree * tree->n_leaves, D, (hipStream_t)stream)) != BR_OK)
+    return s;
   return launch_sde_step(tree, sched, seed, step, D, v_parents, 1, z_nodes, logp_edges, (float*)scratch,
                          (hipStream_t)stream);
 }
