@@ -8,7 +8,7 @@ import torch
 from oracle import dit
 from paper_2509_06040_amd import binding as br
 from paper_2509_06040_amd import synth
-from gpu_util import DEV, bytes_buffer, cond_dev, dev, host, make_model, rel_l2
+from gpu_util import DEV, assert_velocity, bytes_buffer, cond_dev, dev, host, make_model, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -149,14 +149,15 @@ def test_velocity_tiny_fp32_matches_oracle(lib):
     for t, std in ((1.0, 0.02), (0.37, 0.02), (0.05, 0.2)):
         got, ref, _ = _velocity_case(cfg, 2, 5, t, 0, std)
         for b in range(5):
-            assert rel_l2(got[b], ref[b]) <= 1e-4, (t, b, rel_l2(got[b], ref[b]))   # stated fp32 tolerance
+            assert_velocity(cfg, got[b], ref[b], 1e-4, "tiny t=%g b=%d" % (t, b))   # stated fp32 tolerance
 
 
 def test_velocity_fp32_other_shapes(lib):
     # temporal patches, head dim 32, ragged token count
     cfg = synth.model_cfg(2, 64, 2, (3, 4, 6, 10), (2, 2, 2), 5, synth.F32)
     got, ref, _ = _velocity_case(cfg, 3, 4, 0.6, 3, 0.1)
-    assert max(rel_l2(got[b], ref[b]) for b in range(4)) <= 1e-4
+    for b in range(4):
+        assert_velocity(cfg, got[b], ref[b], 1e-4, "fp32 shapes b=%d" % b)
 
 
 def test_velocity_small_bf16_matches_oracle(lib):
@@ -164,7 +165,7 @@ def test_velocity_small_bf16_matches_oracle(lib):
                 synth.model_cfg(1, 256, 2, (16, 2, 8, 12), (1, 2, 2), 70, synth.BF16)):         # d_h 128, L = 166
         got, ref, _ = _velocity_case(cfg, 2, 3, 0.5, 1, 0.05)
         for b in range(3):
-            assert rel_l2(got[b], ref[b]) <= 2e-2, rel_l2(got[b], ref[b])                       # stated bf16 tolerance
+            assert_velocity(cfg, got[b], ref[b], 2e-2, "small bf16 b=%d" % b)                   # stated bf16 tolerance
 
 
 def test_velocity_chunked_batches_agree(lib):

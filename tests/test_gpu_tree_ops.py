@@ -42,6 +42,8 @@ def test_fusion_hand_worked_trees(lib, name):
                                                    (20, (0, 3, 6, 9), 3, 2, 2.0), (16, (3, 6, 9, 12), 4, 2, 300.0),
                                                    (10, (0, 1, 2, 3, 4, 5, 6), 2, 2, 1.0), (6, (), 2, 3, 1.0),
                                                    (5, (1, 3), 1, 5, 1.0),
+                                                   (16, (3, 6, 9, 12), 2, 2, 0.05),            # the large-image workload's trees
+                                                   (16, (4, 8, 12), 2, 1, 0.05),               # the video workload's tree
                                                    (100, (0, 1, 2, 3, 4, 5), 2, 1, 0.3)])      # 6143 nodes: not LDS-cached
 def test_fusion_and_advantages_match_oracle(lib, T, splits, K, C, lp_scale):
     t = br.Tree(T, splits, K, n_tree=C)
@@ -81,7 +83,8 @@ def test_leaf_rewards_match_oracle(lib, kind):
 
 @pytest.mark.parametrize("T,splits,K,C", [(8, (2, 4, 6), 2, 1), (20, (4, 8, 12, 16), 2, 4), (20, (0, 3, 6, 9), 3, 3),
                                           (16, (3, 6, 9, 12), 4, 5), (6, (), 2, 2), (4, (1, 2), 1, 3),
-                                          (12, tuple(range(10)), 2, 2)])
+                                          (12, tuple(range(10)), 2, 2),
+                                          (16, (3, 6, 9, 12), 2, 2), (16, (4, 8, 12), 2, 1)])   # large-image and video trees
 def test_pruned_edge_sets_are_bit_exact(lib, T, splits, K, C):
     t = br.Tree(T, splits, K, n_tree=C)
     o = tree.tree_build(T, splits, K)
@@ -123,7 +126,8 @@ def test_grpo_objective_matches_oracle(lib):
 
 
 @pytest.mark.parametrize("T,splits,K,C", [(8, (2, 4, 6), 2, 1), (20, (4, 8, 12, 16), 2, 4), (20, (0, 3, 6, 9), 3, 3),
-                                          (16, (3, 6, 9, 12), 4, 2), (6, (), 2, 2)])
+                                          (16, (3, 6, 9, 12), 4, 2), (6, (), 2, 2),
+                                          (16, (3, 6, 9, 12), 2, 2), (16, (4, 8, 12), 2, 1)])
 def test_fusion_ess_matches_oracle(lib, T, splits, K, C):
     t, o = br.Tree(T, splits, K, n_tree=C), tree.tree_build(T, splits, K)
     rng = np.random.default_rng(T + K)
