@@ -103,7 +103,7 @@ def test_video_shape_batch_of_eight_matches_oracle_on_sampled_tokens(video_case,
 def test_video_shape_batch_of_eight_agrees_with_single_samples(video_case):
     r = video_case
     cfg, sz = r["cfg"], r["sz"]
-    ws = bytes_buffer(br.workspace_bytes(None, r["model"], 1))
+    ws = bytes_buffer(br.workspace_bytes(None, r["model"], 2))     # sized for the two prompts' conditioning
     for b in (3, 7):                                     # one sample of each prompt, alone
         v1 = torch.empty((1, sz["D"]), device=DEV)
         br.velocity(r["model"], dev(r["z"][b:b + 1]), 0.3, cond_dev(cfg, r["cond"]), r["cidx"][b:b + 1], v1, ws)
