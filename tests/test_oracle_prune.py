@@ -76,6 +76,27 @@ def test_seeded_depth_subset():
     assert prune.depth_mask_seeded(20, 0, 42).sum() == 0 and prune.depth_mask_seeded(5, 5, 1).all()
 
 
+def test_seeded_depth_subset_drops_the_smallest_words():
+    # direction of the selection: every dropped step has a smaller (word, step) than every kept one;
+    # the stored cases list the words and the dropped steps (tests/golden/make_depth_mask_golden.py)
+    import json
+    import os
+    gold = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "depth_mask_seeded.json")))["cases"]
+    assert len(gold) >= 5
+    for g in gold:
+        m = prune.depth_mask_seeded(g["T"], g["n_drop"], g["seed"])
+        assert sorted(np.nonzero(m)[0].tolist()) == g["dropped"], g
+        key = [(g["words"][i], i) for i in range(g["T"])]
+        dropped, keptk = [key[i] for i in range(g["T"]) if m[i]], [key[i] for i in range(g["T"]) if not m[i]]
+        if dropped and keptk:
+            assert max(dropped) < min(keptk)
+    # the image workload's mask (T = 20, 4 drops, seed 42), read off the stored words by eye: the four
+    # smallest are 138049223 (step 7), 830668340 (12), 834821491 (10), 853052770 (11); the next, 1012887007, is step 3
+    assert (gold[0]["T"], gold[0]["n_drop"], gold[0]["seed"]) == (20, 4, 42)
+    assert gold[0]["words"][7] == 138049223 and gold[0]["words"][3] == 1012887007
+    assert list(np.nonzero(prune.depth_mask_seeded(20, 4, 42))[0]) == [7, 10, 11, 12]
+
+
 def test_hybrid_ode_sde_schedule():
     # ablation "Hybrid ODE-SDE": split steps stay SDE, the window adds SDE steps, the rest are ODE steps
     win = prune.depth_mask_window(20, 16, 4, 0, 30, 20)          # steps 16..19
