@@ -277,6 +277,18 @@ br_status br_sde_step(const br_tree* tree, const br_sched* sched, uint64_t seed,
                       int64_t D, const float* v_parents, float* z_nodes, float* logp_edges,
                       void* scratch, size_t scratch_bytes, void* stream);
 
+/* br_sde_step for callers that cannot allocate device memory (code under HIP graph capture,
+ * serving loops, harnesses that forbid hipMalloc): same arguments and results, but the scratch
+ * is an array built into the library (one copy per GPU, held until the process ends) and the
+ * call itself allocates nothing.  BR_EWORKSPACE when br_sde_scratch_bytes(tree, D) exceeds
+ * br_sde_static_scratch_limit() (64 KiB = 8192 leaves over all trees).  All calls
+ * on one GPU share that array: calls that overlap on one GPU (different streams or threads)
+ * race; calls on one stream are safe. */
+size_t br_sde_static_scratch_limit(void);
+br_status br_sde_step_static(const br_tree* tree, const br_sched* sched, uint64_t seed, int32_t step,
+                             int64_t D, const float* v_parents, float* z_nodes, float* logp_edges,
+                             void* stream);
+
 /* Root latents alone: z_nodes rows of all roots <- N(0, I) of (seed, noise_group). */
 br_status br_root_noise(const br_tree* tree, uint64_t seed, const int32_t* noise_group, int64_t D,
                         float* z_nodes, void* stream);

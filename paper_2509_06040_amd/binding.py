@@ -27,7 +27,8 @@ _MATRICES = {n for n in WEIGHT_ORDER if n.endswith("_w")}
 EXPORTS = (
     "br_last_error", "br_tree_build", "br_tree_info", "br_tree_upload", "br_tree_free", "br_model_create", "br_model_free",
     "br_workspace_bytes", "br_rollout", "br_logprob", "br_fuse_advantage", "br_prune", "br_reward_scratch_bytes",
-    "br_leaf_reward", "br_grpo_objective", "br_velocity", "br_sde_scratch_bytes", "br_sde_step", "br_root_noise",
+    "br_leaf_reward", "br_grpo_objective", "br_velocity", "br_sde_scratch_bytes", "br_sde_step", "br_sde_static_scratch_limit",
+    "br_sde_step_static", "br_root_noise",
     "br_noise_stream", "br_depth_mask_window", "br_depth_mask_seeded", "br_mix_schedule", "br_fusion_ess", "br_op_gemm", "br_op_attention",
     "br_op_ln_modulate", "br_profile_enable", "br_profile_read",
 )
@@ -59,7 +60,7 @@ def load():
         raise FileNotFoundError("%s is missing: build it with `python -m paper_2509_06040_amd.build`" % LIB_PATH)
     lib = C.CDLL(LIB_PATH)
     lib.br_last_error.restype = C.c_char_p
-    for name in ("br_workspace_bytes", "br_reward_scratch_bytes", "br_sde_scratch_bytes"):
+    for name in ("br_workspace_bytes", "br_reward_scratch_bytes", "br_sde_scratch_bytes", "br_sde_static_scratch_limit"):
         getattr(lib, name).restype = C.c_size_t
     lib.br_tree_free.restype = None
     lib.br_model_free.restype = None
@@ -236,6 +237,16 @@ def sde_step(tree, sched, seed, step, D, v_parents, z_nodes, logp_edges, scratch
     _check(load().br_sde_step(tree._h, C.byref(s), C.c_uint64(seed), C.c_int32(step), C.c_int64(D), _p(v_parents),
                               _p(z_nodes), _p(logp_edges), _p(scratch),
                               C.c_size_t(scratch.numel() * scratch.element_size()), _stream()))
+
+
+def sde_static_scratch_limit():
+    return load().br_sde_static_scratch_limit()
+
+
+def sde_step_static(tree, sched, seed, step, D, v_parents, z_nodes, logp_edges):
+    s = make_sched(sched)
+    _check(load().br_sde_step_static(tree._h, C.byref(s), C.c_uint64(seed), C.c_int32(step), C.c_int64(D),
+                                     _p(v_parents), _p(z_nodes), _p(logp_edges), _stream()))
 
 
 def root_noise(tree, seed, noise_group, D, z_nodes):

@@ -370,6 +370,49 @@ extern "C" br_status br_sde_step(const br_tree* tree, const br_sched* sched, uin
                          (hipStream_t)stream);
 }
 
+// ---- br_sde_step for callers that cannot allocate: the scratch of the step (the 64-bit
+// words the blocks of a child accumulate its log-prob in) lives in a device array of the library instead of a caller buffer.
+namespace {
+constexpr size_t kStaticScratchBytes = 1u << 16;  // one 64-bit word per child of a step: 8192 children
+static __device__ __align__(256) unsigned char g_sde_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_sde_scratch_ptr[kMaxDevices] = {nullptr};  // device address of the array on each device
+
+br_status static_scratch(float** out) {
+  int dev = 0;
+  BR_HIP(hipGetDevice(&dev));
+  BR_REQUIRE(dev >= 0 && dev < kMaxDevices, BR_EDEVICE, "br_sde_step_static: device index out of range");
+  void* p = __atomic_load_n(&g_sde_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {  // every device holds its own copy of the array at its own address
+    BR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_sde_scratch)));
+    BR_REQUIRE(p != nullptr, BR_EDEVICE, "br_sde_step_static: the scratch array has no device address");
+    __atomic_store_n(&g_sde_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+  }
+  *out = static_cast<float*>(p);
+  return BR_OK;
+}
+}  // namespace
+
+extern "C" size_t br_sde_static_scratch_limit(void) { return kStaticScratchBytes; }
+
+extern "C" br_status br_sde_step_static(const br_tree* tree, const br_sched* sched, uint64_t seed, int32_t step,
+                                        int64_t D, const float* v_parents, float* z_nodes, float* logp_edges,
+                                        void* stream) {
+  BR_REQUIRE(tree && v_parents && z_nodes && logp_edges, BR_EINVAL, "br_sde_step_static: NULL argument");
+  br_status s;
+  if ((s = check_sched(tree, sched, "br_sde_step_static")) != BR_OK) return s;
+  BR_REQUIRE(step >= 0 && step < tree->T, BR_EINVAL, "br_sde_step_static: step outside [0, T)");
+  BR_REQUIRE(D >= 4 && D % 4 == 0, BR_ESHAPE, "br_sde_step_static: D must be a positive multiple of 4");
+  BR_REQUIRE(br_sde_scratch_bytes(tree, D) <= kStaticScratchBytes, BR_EWORKSPACE,
+             "br_sde_step_static: the tree needs more than the 64 KiB of built-in scratch (br_sde_scratch_bytes: "
+             "8 bytes per leaf); use br_sde_step with a caller buffer");
+  float* scratch = nullptr;
+  if ((s = static_scratch(&scratch)) != BR_OK) return s;
+  const long long n_items = (long long)tree->n_tree * tree->n_leaves;
+  if ((s = launch_sde_scratch_reset(scratch, n_items, D, (hipStream_t)stream)) != BR_OK) return s;
+  return launch_sde_step(tree, sched, seed, step, D, v_parents, 1, z_nodes, logp_edges, scratch, (hipStream_t)stream);
+}
+
 extern "C" br_status br_root_noise(const br_tree* tree, uint64_t seed, const int32_t* noise_group, int64_t D,
                                    float* z_nodes, void* stream) {
   BR_REQUIRE(tree && noise_group && z_nodes, BR_EINVAL, "br_root_noise: NULL argument");
