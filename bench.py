@@ -5,15 +5,25 @@ One step = one pass of the whole path over one batch of synthetic prompts:
   br_rollout (tree rollout under the behaviour policy) -> br_leaf_reward ->
   br_fuse_advantage -> br_prune -> br_logprob (re-evaluation of the kept edges
   under perturbed weights) -> br_grpo_objective.
-Workload: the image-shaped tree (DiT 12 blocks, hidden 1024, 16 heads, latent
-16x64x64, 1024+77 tokens, T = 20, splits {4,8,12,16}, K = 2, 4 prompts -> 64
-leaves), with Extreme-4 width pruning and 4 seeded dropped depths.
 
-Prints ONE JSON line: leaf trajectories/s of the whole step, with the roofline
-of the dominant kernel (measured with HIP events around every launch inside the
-timed region) and the CPU oracle timed on a bounded sample beside it.
+Three workload shapes run in one invocation (all synthetic, seeded):
+  image        DiT 12 blocks, hidden 1024, 16 heads, latent 16x64x64, 1024+77 tokens, T = 20,
+               splits {4,8,12,16}, K = 2, 4 prompts -> 64 leaves
+  video        30 blocks, hidden 1536, 12 heads, latent 16x21x60x104, 32760+512 tokens with full
+               attention, T = 16, splits {4,8,12}, 1 prompt -> 8 leaves
+  image_large  24 blocks, hidden 3072, 24 heads, latent 16x128x128, 4096+512 tokens, T = 16,
+               splits {3,6,9,12}, 2 prompts -> 32 leaves                    (the headline)
+each with Extreme-b width pruning (b = leaves/4) and 4 seeded dropped depths.  The headline
+workload is timed for exactly --steps steps after --warmup warm-up steps; image takes the same
+counts (it is cheap), video one warm-up and one timed step (a step is 15-20 s).
+
+Prints ONE JSON line: leaf trajectories/s of the headline workload's whole step, with the roofline
+of its dominant kernel (HIP events around every launch inside the timed region), the flat N*T
+rollout and the CPU oracle (bounded sample) beside it, and under "workloads" the same figures
+for every workload that ran.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -29,35 +39,22 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 GEMM_NAMES = {0: "bias", 1: "bias_gelu", 2: "bias_gate_residual", 3: "patch_embed", 4: "bias_f32", 5: "unpatchify"}
 TILE_NAMES = {4: "256x256 lds-direct", 5: "128x128 lds-direct",
               6: "256x128 lds-direct", 7: "256x256 persistent stream"}
+HEADLINE = "image_large"
+ORDER = ("image", "video", "image_large")
 
 
-# HBM-side traffic per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE, KiB per dispatch averaged over the launches of one step) scaled by what the same counters
-# read for a plain 1 GiB device copy (FETCH_SIZE reads 0.5 GiB -> x2.0; WRITE_SIZE reads 1 GiB -> x1.0);
-# see profiles/hot_kernels_hbm_traffic.md.  Valid only for the kernel sources hashed below.
-TRAFFIC = {
-    "gemm_bf16[bias_gate_residual,256x256 persistent stream]": dict(
-        bytes_per_launch=279020.25 * 1024 * 2.0 + 177344.78 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
-    "gemm_bf16[bias_gelu,256x256 persistent stream]": dict(
-        bytes_per_launch=237943.44 * 1024 * 2.0 + 309737.46 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
-    "gemm_bf16[bias,256x256 persistent stream]": dict(
-        bytes_per_launch=151099.73 * 1024 * 2.0 + 189502.07 * 1024 * 1.0,
-        sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1="4e332a2b8d62cbb2a05cd00a81c10dde937c24ce"),
-    "attn_bf16[d64]": dict(
-        bytes_per_launch=94775.25 * 1024 * 2.0 + 63124.00 * 1024 * 1.0,
-        sources=('attn_bf16.hip',), sha1="fbe6a1e9f145fb7c60c7fe2334196b71d35a5efc"),
-    "ln_modulate": dict(
-        bytes_per_launch=63167.22 * 1024 * 2.0 + 62947.46 * 1024 * 1.0,
-        sources=('dit_kernels.hip', 'common.h'), sha1="fe54c511428b8d901e03fa5064dd54b2441efca3"),
-}
+# HBM-side traffic per launch, from two rocprofv3 --pmc runs of this file on one workload (FETCH_SIZE,
+# then WRITE_SIZE, KiB per dispatch averaged over the launches of one step), each scaled by what the
+# same counter reads for a plain 1 GiB device copy; see profiles/hot_kernels_hbm_traffic.md.  Keyed
+# by (workload, kernel label); valid only for the kernel sources hashed beside the figures.
+TRAFFIC = {}
 
 
-def measured_traffic(label):
-    """Counter-measured HBM bytes per launch, or None if the kernel changed since the counters were taken."""
+def measured_traffic(workload, label):
+    """Counter-measured HBM bytes per launch, or None if there are none for this workload and kernel
+    or the kernel sources changed since the counters were taken."""
     import hashlib
-    t = TRAFFIC.get(label)
+    t = TRAFFIC.get("%s|%s" % (workload, label))
     if t is None:
         return None
     h = hashlib.sha1()
@@ -77,35 +74,17 @@ def kernel_label(kid):
     return "attn_bf16[d%d]" % (kid - 100)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="image", choices=["image", "tiny", "image_large", "video"],
-                    help="image is the workload of the headline metric; the others are extra shapes")
-    ap.add_argument("--splits", default=None, help="comma-separated split steps replacing the workload's (extra shapes: "
-                    "the paper's Dense 0,3,6,9 / Mixed 0,4,8,12 / Sparse 0,5,10,15 presets, five splits, ...)")
-    ap.add_argument("--branch", type=int, default=None, help="branching factor K replacing the workload's (3 -> 81, 4 -> 256 leaves)")
-    ap.add_argument("--prompts", type=int, default=None, help="number of prompts (independent trees) replacing the workload's")
-    ap.add_argument("--no-kernel-events", action="store_true", help="do not time single launches in the timed region")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-flat", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: the measurement covers one GPU only (conditions are independent trees and would shard "
-                 "across GPUs without collectives); run with --gpus 1")
+def progress(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
 
+
+def bench_workload(name, steps, warmup, args, want_flat, want_cpu):
+    """Times `steps` steps of workload `name` (after `warmup` untimed ones) and returns its figures."""
     import torch
     from paper_2509_06040_amd import binding as br
     from paper_2509_06040_amd import synth
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    br.load()
     dev = "cuda"
-    wl = dict(synth.WORKLOADS[args.workload])
+    wl = dict(synth.WORKLOADS[name])
     if args.splits is not None:
         wl["splits"] = tuple(int(x) for x in args.splits.split(",") if x != "")
     if args.branch is not None:
@@ -118,14 +97,22 @@ def main():
     latent = (cfg["latent_c"], cfg["latent_t"], cfg["latent_h"], cfg["latent_w"])
     tdt = torch.bfloat16 if cfg["dtype"] == synth.BF16 else torch.float32
 
-    W = synth.make_weights(cfg, 0)
-    W2 = synth.perturb_weights(cfg, W, 11, 0.002)
-    model = br.Model(cfg, br.upload_weights(cfg, W))
-    model2 = br.Model(cfg, br.upload_weights(cfg, W2))
+    # weights: the small networks are drawn on the host (the same arrays feed the oracle below), the
+    # multi-billion-parameter ones on the device
+    W = None
+    if name in ("image", "tiny"):
+        W = synth.make_weights(cfg, 0)
+        model = br.Model(cfg, br.upload_weights(cfg, W))
+        model2 = br.Model(cfg, br.upload_weights(cfg, synth.perturb_weights(cfg, W, 11, 0.002)))
+    else:
+        Wd = synth.device_weights(cfg, 0, dev)
+        model = br.Model(cfg, Wd)
+        model2 = br.Model(cfg, synth.device_perturb_weights(cfg, Wd, 11, 0.002, dev))
+        del Wd
     cond_np = synth.cond_tokens(cfg, C)
     cond = torch.from_numpy(cond_np).to(dev).to(tdt)
     sched = synth.schedule(T, wl["kappa"], logp_mean=True)
-    tree = br.Tree(T, wl["splits"], wl["K"], n_tree=C)
+    tree = br.Tree(T, wl["splits"], wl["K"], n_tree=C).upload()
     n_leaves = C * tree.n_leaves
     n = C * tree.n_nodes
     groups = list(range(C))
@@ -168,32 +155,26 @@ def main():
             ev[3].record()
         return ev, nk
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(synth.SAMPLER_SEED + i, False)
     torch.cuda.synchronize()
     if not args.no_kernel_events:
         br.profile_enable(True)
         br.profile_read()
     t0 = time.perf_counter()
-    evs = [step(synth.SAMPLER_SEED + 100 + i, True) for i in range(args.steps)]
+    evs = [step(synth.SAMPLER_SEED + 100 + i, True) for i in range(steps)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = {}
     if not args.no_kernel_events:
         prof = br.profile_read()
         br.profile_enable(False)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     nk = evs[-1][1]
-    for name, a, b in (("rollout", 0, 1), ("reward_fuse_prune", 1, 2), ("logprob_objective", 2, 3)):
-        phase_ms[name] = float(np.mean([e[0][a].elapsed_time(e[0][b]) for e in evs]))
+    for pname, a, b in (("rollout", 0, 1), ("reward_fuse_prune", 1, 2), ("logprob_objective", 2, 3)):
+        phase_ms[pname] = float(np.mean([e[0][a].elapsed_time(e[0][b]) for e in evs]))
     value = n_leaves / (ms_per_step * 1e-3)
-
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+    progress("%s: %d steps, %.1f ms/step" % (name, steps, ms_per_step))
 
     # ---- roofline of the dominant kernel (largest total time among the instrumented ones)
     kernels = {}
@@ -209,7 +190,7 @@ def main():
         dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
         k = kernels[dom]
         roofline = dict(kernel=dom, bound=k["bound"], achieved=k["achieved"], peak=PEAK_BF16_TFLOPS if k["bound"] == "mfma" else PEAK_HBM_GBS,
-                        unit=k["unit"], frac=k["frac"], traffic=measured_traffic(dom), avg_launch_us=k["avg_us"], launches=k["launches"])
+                        unit=k["unit"], frac=k["frac"], traffic=measured_traffic(name, dom), avg_launch_us=k["avg_us"], launches=k["launches"])
         mf = [v for v in kernels.values() if v["bound"] == "mfma"]
         tot_flop = sum(v["achieved"] * v["total_ms"] for v in mf)
         tot_ms = sum(v["total_ms"] for v in mf)
@@ -229,8 +210,8 @@ def main():
         return a.elapsed_time(b) * 1e3 / reps
 
     def sde_kernel_us(fn, reps=20):
-        """Average duration of the fused step kernel alone (HIP events on the launch stream around that kernel;
-        the call also launches the small kernel that sums the per-block log-prob partials)."""
+        """Average duration of the fused step kernel alone: a HIP event pair on the launch stream around
+        that kernel (the pair itself costs a few microseconds, see `event_pair_floor_us`)."""
         fn()
         torch.cuda.synchronize()
         br.profile_enable(True)
@@ -244,40 +225,28 @@ def main():
 
     small_calls = {}
     sde_scratch = torch.empty(max(256, br.sde_scratch_bytes(tree, D)), dtype=torch.uint8, device=dev)
-    steps = [T - 1] + ([max(wl["splits"])] if wl["K"] > 1 and len(wl["splits"]) else [])
-    for name, i in zip(("sde_step_largest_frontier", "sde_step_last_split"), steps):
+    # what the event pair reads around the same kernel when it has next to nothing to do (one parent, 4 KB)
+    ftree = br.Tree(T, (), 1, n_tree=1)
+    fz, flp = torch.zeros((ftree.n_nodes, 1024), device=dev), torch.zeros(ftree.n_nodes, device=dev)
+    fv = torch.zeros((1, 1024), device=dev)
+    floor_us = sde_kernel_us(lambda: br.sde_step(ftree, sched, 5, 0, 1024, fv, fz, flp, sde_scratch))
+    small_calls["event_pair_floor_us"] = round(floor_us, 2)
+    del ftree, fz, flp, fv
+    split_steps = [s_ for s_ in wl["splits"] if s_ < T] if wl["K"] > 1 else []
+    sde_steps = [T - 1] + ([max(split_steps)] if split_steps else [])
+    for cname, i in zip(("sde_step_largest_frontier", "sde_step_last_split"), sde_steps):
         parents, children = C * int(tree.width[i]), C * int(tree.width[i + 1])
         vpar = torch.randn((parents, D), device=dev)
         call = lambda: br.sde_step(tree, sched, 5, i, D, vpar, z, logp, sde_scratch)
         us, kus = timed_us(call), sde_kernel_us(call)
         nbytes = (2 * parents + children) * 4.0 * D + 4.0 * children          # read z, v per parent; write children
-        small_calls[name] = dict(step=int(i), parents=parents, children=children, call_us=round(us, 2),
-                                 kernel_us=round(kus, 2), algorithmic_bytes=int(nbytes),
-                                 achieved_GBps=round(nbytes / kus / 1e3, 1),
-                                 frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4))
+        small_calls[cname] = dict(step=int(i), parents=parents, children=children, D=int(D), call_us=round(us, 2),
+                                  kernel_us=round(kus, 2), algorithmic_bytes=int(nbytes),
+                                  achieved_GBps=round(nbytes / kus / 1e3, 1),
+                                  frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4),
+                                  frac_of_hbm_peak_less_event_floor=round(
+                                      nbytes / max(kus - floor_us, 1e-3) / 1e3 / PEAK_HBM_GBS, 4))
         del vpar
-    # the same kernel on the largest frontier of the other workload shapes (their networks are not run here)
-    for other in ("image_large", "video"):
-        if other == args.workload:
-            continue
-        ow = synth.WORKLOADS[other]
-        oD = synth.model_sizes(ow["model"])["D"]
-        otree = br.Tree(ow["T"], ow["splits"], ow["K"], n_tree=ow["n_cond"])
-        oz = torch.empty((ow["n_cond"] * otree.n_nodes, oD), device=dev).normal_()
-        olp = torch.empty(ow["n_cond"] * otree.n_nodes, device=dev)
-        osched = synth.schedule(ow["T"], ow["kappa"], logp_mean=True)
-        oscr = torch.empty(max(256, br.sde_scratch_bytes(otree, oD)), dtype=torch.uint8, device=dev)
-        i = ow["T"] - 1
-        parents = ow["n_cond"] * int(otree.width[i])
-        vpar = torch.randn((parents, oD), device=dev)
-        call = lambda: br.sde_step(otree, osched, 5, i, oD, vpar, oz, olp, oscr)
-        us, kus = timed_us(call), sde_kernel_us(call)
-        nbytes = 3 * parents * 4.0 * oD + 4.0 * parents
-        small_calls["sde_step_largest_frontier[%s]" % other] = dict(
-            step=int(i), parents=parents, children=parents, D=int(oD), call_us=round(us, 2), kernel_us=round(kus, 2),
-            algorithmic_bytes=int(nbytes), achieved_GBps=round(nbytes / kus / 1e3, 1),
-            frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4))
-        del oz, olp, oscr, vpar, otree
     us = timed_us(lambda: br.leaf_reward(tree, z, kind, w_rew, lam, latent, rew, rs))
     nbytes = 4.0 * D * n_leaves + 4.0 * D
     small_calls["leaf_reward"] = dict(leaves=n_leaves, us=round(us, 2), algorithmic_bytes=int(nbytes),
@@ -287,12 +256,11 @@ def main():
         lambda: br.fuse_advantage(tree, rew, logp, 1.0, 1e-8, 0, synth.ADV_CLIP, rbar, adv)), 2), bound="launch latency")
     small_calls["prune"] = dict(us=round(timed_us(
         lambda: br.prune(tree, rew, br.PRUNE_EXTREME, b_extreme, depth_mask, kept, n_kept)), 2), bound="launch latency")
-    step(synth.SAMPLER_SEED + 100 + args.steps - 1, False)     # leave the arena as the last timed step left it
+    step(synth.SAMPLER_SEED + 100 + steps - 1, False)     # leave the arena as the last timed step left it
 
     # ---- model FLOPs of a step (2MNK per GEMM, 4 L^2 H per attention block) / wall time
     fwd_flop = NB * (24.0 * L * H * H + 4.0 * L * L * H) + 4.0 * sz["n_img"] * sz["patch_dim"] * H
     n_eval_roll = C * int(sum(tree.width[:T]))
-    depth_of = tree.depth
     par = set()
     for g in (kept[:nk].cpu().numpy() if nk else []):
         cc, nn_ = divmod(int(g), tree.n_nodes)
@@ -303,31 +271,34 @@ def main():
 
     # ---- flat N*T sequential rollout on the same GPU, same kernels (K = 1 trees)
     flat = None
-    if not args.no_flat:
+    if want_flat:
         ftree = br.Tree(T, (), 1, n_tree=n_leaves)
         fz = torch.empty((n_leaves * ftree.n_nodes, D), device=dev)
         flp = torch.empty(n_leaves * ftree.n_nodes, device=dev)
         fcond = cond.repeat_interleave(tree.n_leaves, dim=0).contiguous()
         fgroups = [c for c in range(C) for _ in range(tree.n_leaves)]     # "init same noise" per prompt
         fws = torch.empty(br.workspace_bytes(ftree, model, n_leaves), dtype=torch.uint8, device=dev)
-        br.rollout(ftree, model, sched, 1, fgroups, fcond, fz, flp, None, fws)
+        cheap = name in ("image", "tiny")
+        if cheap:                                                         # a warm-up run where it costs little
+            br.rollout(ftree, model, sched, 1, fgroups, fcond, fz, flp, None, fws)
         torch.cuda.synchronize()
         f0 = time.perf_counter()
-        reps = 2
+        reps = 2 if cheap else 1
         for i in range(reps):
             br.rollout(ftree, model, sched, 2 + i, fgroups, fcond, fz, flp, None, fws)
         torch.cuda.synchronize()
         fms = (time.perf_counter() - f0) * 1e3 / reps
-        flat = dict(ms=round(fms, 2), leaf_traj_per_s=round(n_leaves / (fms * 1e-3), 2),
+        flat = dict(ms=round(fms, 2), leaf_traj_per_s=round(n_leaves / (fms * 1e-3), 3),
                     tree_rollout_ms=round(phase_ms["rollout"], 2),
-                    tree_rollout_leaf_traj_per_s=round(n_leaves / (phase_ms["rollout"] * 1e-3), 2),
+                    tree_rollout_leaf_traj_per_s=round(n_leaves / (phase_ms["rollout"] * 1e-3), 3),
                     speedup_tree_vs_flat=round(fms / phase_ms["rollout"], 3), network_evals_flat=n_leaves * T,
                     network_evals_tree=n_eval_roll)
-        del fz, flp, fws
+        del fz, flp, fws, fcond
+        progress("%s: flat rollout %.1f ms" % (name, fms))
 
     # ---- the CPU oracle on a bounded sample, extrapolated to a step
     cpu = None
-    if not args.no_cpu_baseline:
+    if want_cpu:
         from oracle import dit as odit
         from oracle import philox as ophilox
         from oracle import sde as osde
@@ -338,38 +309,112 @@ def main():
         except Exception:
             pass
         rnd = odit.round_bf16 if cfg["dtype"] == synth.BF16 else odit.identity
-        n_sample = 3 if args.workload == "image" else 1    # about 12 s of oracle work on the image shape
+        if W is not None:          # whole network evaluations at full size
+            n_sample, ocfg, oW, scale = (3 if name == "image" else 1), cfg, W, 1.0
+            what = "%d oracle network evaluations"
+        else:                      # one block of the network at full size, times the number of blocks
+            ocfg = dict(cfg)
+            ocfg["n_blocks"] = 1
+            n_sample, oW, scale = 1, synth.make_weights(ocfg, 0), float(NB)
+            what = "%d oracle evaluation of ONE of the " + str(NB) + " blocks (with the embedding and final layers; x" + str(NB) + ")"
         zs = synth.random_latents(n_sample, D, 3)
         c0 = time.perf_counter()
         for i in range(n_sample):
-            v = odit.forward(cfg, W, zs[i:i + 1], float(sched["t"][3 + i]), cond_np, [i % C], act_round=rnd)
+            v = odit.forward(ocfg, oW, zs[i:i + 1], float(sched["t"][3 + i]), cond_np, [i % C], act_round=rnd)
         c1 = time.perf_counter()
         mu = osde.drift_mean(zs[0].astype(np.float64), v[0], sched["t"][3], sched["t"][4], sched["sigma"][3])
         _, std = osde.step_coefficients(sched["t"][3], sched["t"][4], sched["sigma"][3])
         xi = ophilox.normals(1, 5, 3, ophilox.TAG_ETA, D)
         osde.transition_logp(mu + std * xi, mu, std, True)
         c2 = time.perf_counter()
-        per_eval, per_sde = (c1 - c0) / n_sample, c2 - c1
+        per_eval, per_sde = (c1 - c0) / n_sample * scale, c2 - c1
         est = (n_eval_roll + n_eval_lp) * per_eval + (n - C + nk) * per_sde
-        cpu = dict(value=round(n_leaves / est, 5), unit="leaf trajectories/s", cores=int(threads), kind="oracle",
-                   sample="%d oracle network evaluations (%.2f s each) + 1 oracle SDE step/log-prob (%.3f s) at full "
-                          "size, extrapolated to the %d evaluations and %d transitions of one step"
-                          % (n_sample, per_eval, per_sde, n_eval_roll + n_eval_lp, n - C + nk))
+        cpu = dict(value=round(n_leaves / est, 6), unit="leaf trajectories/s", cores=int(threads), kind="oracle",
+                   sample=(what % n_sample) + " (%.2f s per whole evaluation) + 1 oracle SDE step/log-prob (%.3f s) at "
+                          "full size, extrapolated to the %d evaluations and %d transitions of one step"
+                          % (per_eval, per_sde, n_eval_roll + n_eval_lp, n - C + nk))
+        progress("%s: oracle sample %.1f s" % (name, c2 - c0))
 
-    out = dict(metric="leaf trajectories/sec (tree vs flat N*T rollout); DiT-fwd MFMA util %", value=round(value, 3),
-               unit="leaf trajectories/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
-               ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype="bf16" if cfg["dtype"] == synth.BF16 else "f32", data="synthetic",
+    out = dict(value=round(value, 4), unit="leaf trajectories/s", steps=steps, warmup=warmup,
+               ms_per_step=round(ms_per_step, 3),
+               dtype="bf16" if cfg["dtype"] == synth.BF16 else "f32",
                config=dict(workload="%s tree: DiT %d blocks hidden %d, L=%d, D=%d, T=%d splits %s K=%d, %d prompts x %d "
                                     "leaves; Extreme-%d width pruning + %d seeded dropped depths, log-prob "
                                     "re-evaluation of %d kept edges under perturbed weights"
-                                    % (args.workload, NB, H, L, D, T, list(wl["splits"]), wl["K"], C, tree.n_leaves,
+                                    % (name, NB, H, L, D, T, list(wl["splits"]), wl["K"], C, tree.n_leaves,
                                        b_extreme, int(depth_mask.sum()), nk),
                            prompts=C, leaves_per_prompt=int(tree.n_leaves), n_nodes=int(tree.n_nodes)),
                phase_ms={k: round(v, 3) for k, v in phase_ms.items()},
                mfma_util_step=round(step_mfma_util, 4), mfma_util_rollout=round(rollout_mfma_util, 4),
                network_evals=dict(rollout=n_eval_roll, logprob=n_eval_lp, flop_per_eval=fwd_flop),
                roofline=roofline, kernels=kernels, small_calls=small_calls, flat_rollout=flat, cpu_baseline=cpu)
+    del model, model2, z, ws, cond
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="all", choices=["all", "image", "tiny", "image_large", "video"],
+                    help="all: image, video and image_large in one run, image_large being the headline; "
+                         "a single name: only that workload, as the headline")
+    ap.add_argument("--video-steps", type=int, default=1, help="timed steps of the video workload when it is not the headline")
+    ap.add_argument("--splits", default=None, help="comma-separated split steps replacing the workload's (extra shapes: "
+                    "the paper's Dense 0,3,6,9 / Mixed 0,4,8,12 / Sparse 0,5,10,15 presets, five splits, ...)")
+    ap.add_argument("--branch", type=int, default=None, help="branching factor K replacing the workload's (3 -> 81, 4 -> 256 leaves)")
+    ap.add_argument("--prompts", type=int, default=None, help="number of prompts (independent trees) replacing the workload's")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not time single launches in the timed region")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-flat", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: the measurement covers one GPU only (conditions are independent trees and would shard "
+                 "across GPUs without collectives); run with --gpus 1")
+
+    import torch
+    from paper_2509_06040_amd import binding as br
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    br.load()
+
+    names = ORDER if args.workload == "all" else (args.workload,)
+    head = HEADLINE if args.workload == "all" else args.workload
+    results = {}
+    for name in names:
+        is_head = name == head
+        if is_head or name == "image":
+            steps, warmup = args.steps, args.warmup
+        else:                                   # video beside the headline: a step takes 15-20 s
+            steps, warmup = args.video_steps, 1
+        results[name] = bench_workload(name, steps, warmup, args,
+                                       want_flat=not args.no_flat and (is_head or name == "image"),
+                                       want_cpu=not args.no_cpu_baseline and is_head)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
+    h = results[head]
+    out = dict(metric="leaf trajectories/sec (tree vs flat N*T rollout); DiT-fwd MFMA util %", value=h["value"],
+               unit="leaf trajectories/s", n_gpus=1, steps=h["steps"], warmup=h["warmup"], ms_per_step=h["ms_per_step"],
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype=h["dtype"], data="synthetic",
+               config=h["config"], phase_ms=h["phase_ms"], mfma_util_step=h["mfma_util_step"],
+               mfma_util_rollout=h["mfma_util_rollout"], network_evals=h["network_evals"], roofline=h["roofline"],
+               kernels=h["kernels"], small_calls=h["small_calls"], flat_rollout=h["flat_rollout"],
+               cpu_baseline=h["cpu_baseline"],
+               workloads={k: {f: v[f] for f in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "phase_ms",
+                                                "mfma_util_step", "mfma_util_rollout", "network_evals", "roofline",
+                                                "kernels", "small_calls", "flat_rollout")}
+                          for k, v in results.items() if k != head})
     print(json.dumps(out))
 
 

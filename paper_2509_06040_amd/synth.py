@@ -159,3 +159,37 @@ def reward_vector(n, seed):
 
 def random_latents(n, D, seed):
     return np.random.default_rng(seed).standard_normal((n, D), dtype=np.float32)
+
+
+def device_weights(cfg, seed, device="cuda", std=0.02):
+    """The distribution of make_weights drawn on the device with a seeded torch generator, in the
+    dtypes the library takes (matrices in the model dtype, biases and `pos` fp32): for networks
+    whose billions of parameters take minutes to draw on the host.  Not the numbers of
+    make_weights; used where nothing is compared with a host copy of the same weights."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    mat = torch.bfloat16 if cfg["dtype"] == BF16 else torch.float32
+    W = {}
+    for name, shape, is_mat in weight_shapes(cfg):
+        if name == "pos":
+            W[name] = torch.from_numpy(positional_table(*shape)).to(device)
+            continue
+        a = torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std
+        W[name] = a.to(mat).contiguous() if is_mat else a.contiguous()
+    return W
+
+
+def device_perturb_weights(cfg, W, seed, std, device="cuda"):
+    """theta' = theta + N(0, std^2) on every matrix and bias of a device_weights dict."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    out = {}
+    for name, shape, is_mat in weight_shapes(cfg):
+        if name == "pos":
+            out[name] = W[name]
+            continue
+        a = W[name].float() + torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std
+        out[name] = a.to(W[name].dtype).contiguous()
+    return out
