@@ -76,9 +76,24 @@ __device__ inline bool stream_tile(int wg, int nwg, int j, int tiles_m, int tile
 template <int MODE, typename TOUT>
 __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __restrict__ A, int lda,
                                                                const bf16* __restrict__ W, int ldw, int M, int N, int K,
-                                                               int tiles_m, int tiles_n, int group_n,
+                                                               int tiles_m, int tiles_n, int group_n, int stagger_slack, int stagger_crit,
                                                                Epilogue<MODE, TOUT> epi) {
   const int tid = threadIdx.x, lane = tid & 63;
+  // Workgroups that start together stay in step tile after tile, so the epilogues of the 32
+  // workgroups of a compute die hit that die's memory port in one burst per round, with the port
+  // idle in between.  Shifting groups of workgroups against each other spreads that traffic.
+  // The four workgroups that share a row panel of A (consecutive ids on a die) keep one phase,
+  // so they still fetch the panel together.  A workgroup whose tile list is one shorter than
+  // the longest on its die starts up to 7 * stagger_slack ticks late (10 ns units) at no cost
+  // to the launch; the others start up to 7 * stagger_crit ticks late.
+  if (stagger_slack > 0 || stagger_crit > 0) {
+    const int nt = tiles_m * tiles_n, x = blockIdx.x & 7, i = blockIdx.x >> 3, per_x = ((int)gridDim.x - x + 7) >> 3;
+    const int cnt = nt / 8 + (x < nt % 8 ? 1 : 0);
+    const int n_mine = i < cnt ? (cnt - i + per_x - 1) / per_x : 0, n_max = (cnt + per_x - 1) / per_x;
+    const unsigned long long wait = (unsigned long long)((i >> 2) & 7) * (unsigned)(n_mine < n_max ? stagger_slack : stagger_crit);
+    const unsigned long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
+  }
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wv % WGM) * WTM, wn0 = (wv / WGM) * WTN;
   const int l32 = lane & 31, lh = lane >> 5;
@@ -262,7 +277,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_stream_kernel(const bf16* __res
 
 template <int MODE, typename TOUT>
 static br_status stream_launch(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
-                               int group_n, hipStream_t st) {
+                               int group_n, int stagger_slack, int stagger_crit, hipStream_t st) {
   Epilogue<MODE, TOUT> epi{ea};
   const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
   // Default walk: column groups of 4.  The 32 tiles an XCD works on at once then span 8 row
@@ -273,7 +288,7 @@ static br_status stream_launch(const bf16* A, int lda, const bf16* W, int ldw, i
   const int nt = tiles_m * tiles_n;
   const int grid = nt < n_cu ? nt : n_cu;
   hipLaunchKernelGGL((gemm_bf16_stream_kernel<MODE, TOUT>), dim3(grid), dim3(512), 0, st, A, lda, W, ldw, M, N, K,
-                     tiles_m, tiles_n, group_n, epi);
+                     tiles_m, tiles_n, group_n, stagger_slack, stagger_crit, epi);
   BR_LAUNCH_CHECK();
   return BR_OK;
 }
@@ -284,16 +299,18 @@ bool gemm_stream_supported(int M, int N, int K, size_t bytes_a, size_t bytes_w) 
 }
 
 br_status launch_gemm_bf16_stream(int mode, const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K,
-                                  const EpiArgs& ea, int group_n, hipStream_t st) {
+                                  const EpiArgs& ea, int group_n, int stagger_slack, int stagger_crit, hipStream_t st) {
+  BR_REQUIRE(stagger_slack >= 0 && stagger_slack <= 20000 && stagger_crit >= 0 && stagger_crit <= 20000, BR_EINVAL,
+             "streaming gemm: stagger out of range");
   BR_REQUIRE(gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2), BR_ESHAPE,
              "streaming gemm: needs K % 128 == 0 and operands below 4 GiB");
   switch (mode) {
-    case EPI_BIAS: return stream_launch<EPI_BIAS, bf16>(A, lda, W, ldw, M, N, K, ea, group_n, st);
-    case EPI_BIAS_GELU: return stream_launch<EPI_BIAS_GELU, bf16>(A, lda, W, ldw, M, N, K, ea, group_n, st);
-    case EPI_BIAS_GATE_RES: return stream_launch<EPI_BIAS_GATE_RES, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
-    case EPI_PATCH_EMBED: return stream_launch<EPI_PATCH_EMBED, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
-    case EPI_BIAS_F32: return stream_launch<EPI_BIAS_F32, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
-    case EPI_UNPATCH: return stream_launch<EPI_UNPATCH, float>(A, lda, W, ldw, M, N, K, ea, group_n, st);
+    case EPI_BIAS: return stream_launch<EPI_BIAS, bf16>(A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
+    case EPI_BIAS_GELU: return stream_launch<EPI_BIAS_GELU, bf16>(A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
+    case EPI_BIAS_GATE_RES: return stream_launch<EPI_BIAS_GATE_RES, float>(A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
+    case EPI_PATCH_EMBED: return stream_launch<EPI_PATCH_EMBED, float>(A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
+    case EPI_BIAS_F32: return stream_launch<EPI_BIAS_F32, float>(A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
+    case EPI_UNPATCH: return stream_launch<EPI_UNPATCH, float>(A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
   }
   return fail(BR_EINVAL, "gemm: unknown epilogue");
 }
