@@ -40,8 +40,18 @@ static __device__ inline const char* uniform_ptr(const char* p) {
   return reinterpret_cast<const char*>(((unsigned long long)hi << 32) | lo);
 }
 
-// slot permutation of the V tile: 16-byte chunk c of row r sits in slot c ^ v_swz(r)
-__device__ inline int v_swz(int r) { return ((r & 1) << 2) | ((r >> 1) & 3); }
+// Slot permutations of the K and V tiles: 16-byte chunk c of row r sits in slot c ^ swz(r).
+// The LDS has 64 banks of 4 bytes; a 16-byte read is served 16 lanes at a time and an 8-byte
+// read 32 lanes at a time, conflict-free when those lanes cover all 256 bytes of a bank row.
+//   K (ds_read_b128, lanes 0..15 = 16 consecutive rows at one chunk index): with 256-byte rows
+//   the rows must land in 16 different slots, with 128-byte rows (two per bank row) row pairs in 8.
+//   V (transposing 8-byte reads, 32 lanes = 4 consecutive rows x 4 consecutive chunks): with
+//   256-byte rows the four rows take the four groups of 4 slots, with 128-byte rows the rows
+//   r and r + 2, which share a bank row, take different halves.
+template <int DH>
+__device__ inline int k_swz(int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); }
+template <int DH>
+__device__ inline int v_swz(int r) { return DH == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); }
 
 // With at most 256 registers a wave (two waves per SIMD) the compiler keeps the MFMA results in
 // ordinary vector registers, where the softmax works on them directly (accumulation registers
@@ -54,7 +64,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
   constexpr int DB = DH / 32;   // 32-row blocks of O^T
   constexpr int RPI = 64 / CH;              // rows covered by one 1 KB load
   constexpr int LPW = KV_TILE / RPI / 4;    // loads per wave, tile and operand
-  constexpr int NPAR = RPI == 8 ? 1 : 2;    // distinct (row & 7) patterns among a wave's loads
+  constexpr int NPAR = RPI == 8 ? 2 : 4;    // distinct slot patterns among a wave's loads (the swizzle period is 16 rows)
   constexpr int ROW_B = CH * 16;            // bytes per row
   constexpr int TILE_B = KV_TILE * ROW_B;
   __shared__ __attribute__((aligned(1024))) char sK[2][TILE_B];
@@ -105,9 +115,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
   unsigned koff[NPAR], voff[NPAR];
 #pragma unroll
   for (int par = 0; par < NPAR; ++par) {
-    const int r7 = ((RPI * par) & 7) + lrow;
-    koff[par] = lrow * ldb + (H + (slot ^ r7) * 8) * 2;
-    voff[par] = lrow * ldb + (2 * H + (slot ^ v_swz(r7)) * 8) * 2;
+    const int r16 = ((RPI * par) & 15) + lrow;  // row of the tile, modulo the swizzle period
+    koff[par] = lrow * ldb + (H + (slot ^ k_swz<DH>(r16)) * 8) * 2;
+    voff[par] = lrow * ldb + (2 * H + (slot ^ v_swz<DH>(r16)) * 8) * 2;
   }
   auto issue = [&](int k0, int buf) {
     const unsigned kdst = (unsigned)(uintptr_t)BR_LPTR(sK[buf]) + wv * LPW * 1024;
@@ -129,13 +139,13 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
 #pragma unroll
       for (int t = 0; t < LPW; ++t) {
         const int row = (wv * LPW + t) * RPI + lrow;
-        const unsigned off = (unsigned)min(k0 + row, L - 1) * ldb + (H + (slot ^ (row & 7)) * 8) * 2;
+        const unsigned off = (unsigned)min(k0 + row, L - 1) * ldb + (H + (slot ^ k_swz<DH>(row)) * 8) * 2;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kdst + t * 1024), "v"(off), "s"(blk) : "memory", "m0");
       }
 #pragma unroll
       for (int t = 0; t < LPW; ++t) {
         const int row = (wv * LPW + t) * RPI + lrow;
-        const unsigned off = (unsigned)min(k0 + row, L - 1) * ldb + (2 * H + (slot ^ v_swz(row & 7)) * 8) * 2;
+        const unsigned off = (unsigned)min(k0 + row, L - 1) * ldb + (2 * H + (slot ^ v_swz<DH>(row)) * 8) * 2;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vdst + t * 1024), "v"(off), "s"(blk) : "memory", "m0");
       }
     }
@@ -149,7 +159,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
 #pragma unroll
   for (int d = 0; d < DB; ++d) {
     const int chunk = d * 4 + 2 * g1 + ((jj & 3) >> 1);
-    vaddr[d] = vrow * ROW_B + (chunk ^ v_swz(vrow)) * 16 + 8 * (jj & 1);
+    vaddr[d] = vrow * ROW_B + (chunk ^ v_swz<DH>(vrow)) * 16 + 8 * (jj & 1);
   }
 
   // Two LDS buffers, one barrier per tile: the next tile is fetched while the current one is
@@ -183,7 +193,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int c = ks * 2 + lh;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ (row & 7))) * 16]);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
       }
     }
