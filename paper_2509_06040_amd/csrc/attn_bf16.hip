@@ -206,22 +206,23 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
           if (key >= L) s[kb][r] = -INFINITY;
         }
     }
-    // running maximum in the raw score domain (the scale is positive); the scale is folded
-    // into the exponent: p = exp2(s c - m c)
+    // Reference maximum in the raw score domain (the scale is positive); the scale is folded into
+    // the exponent: p = exp2(s c - m c).  Softmax does not care which reference m is subtracted as
+    // long as numerator and denominator use the same one, so the reference follows the running
+    // maximum lazily: it moves (and the accumulators are rescaled, 1 + DH/2 multiplications per
+    // lane) only when some query of the wave has seen a score more than kSlack above it, i.e.
+    // when a probability would exceed 2^kSlack.  With an exact running maximum nearly every tile
+    // of a sequence rescales (one of 32 queries finds a new maximum), which was a third of the
+    // kernel's vector instructions -- and these are not hidden behind the matrix instructions.
+    constexpr float kSlack = 8.f;
     float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float mc = m_new * scale_log2;
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
-    // the accumulators are rescaled only when some query of this wave saw a new maximum
-    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+    if (__builtin_amdgcn_ballot_w64((mx - m_run) * scale_log2 > kSlack) != 0) {   // (-inf at the start: always)
+      const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
       l_run *= alpha;
 #pragma unroll
@@ -230,6 +231,11 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
         for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
       m_run = m_new;
     }
+    const float mc = m_run * scale_log2;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
 
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
     const char __attribute__((address_space(3)))* vt = (const char __attribute__((address_space(3)))*)BR_LPTR(sV[buf]);
