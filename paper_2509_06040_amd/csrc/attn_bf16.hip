@@ -176,10 +176,13 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
   // One key tile.  NKB: 32-key blocks of the tile that hold any key at all (2, or 1 in a short
   // last tile); MASK: the tile runs past the end of the sequence.  Only the last tile of a
   // ragged sequence is compiled with masking, so the loop over full tiles carries none of it.
-  auto tile = [&](int it, auto NKBc, auto MASKc) {
+  // BUF: the LDS buffer of the tile (it & 1) as a constant, so that fragment addresses are a
+  // loop-invariant per-lane register plus an immediate.
+  auto tile = [&](int it, auto NKBc, auto MASKc, auto BUFc) {
     constexpr int NKB = decltype(NKBc)::value;
     constexpr bool MASK = decltype(MASKc)::value;
-    const int k0 = it * KV_TILE, buf = it & 1;
+    constexpr int buf = decltype(BUFc)::value;
+    const int k0 = it * KV_TILE;
     // the other buffer was last read one tile ago, before the previous barrier
     issue(min(it + 1, nkv - 1) * KV_TILE, buf ^ 1);
 
@@ -270,11 +273,24 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
   using K1 = std::integral_constant<int, 1>;
   using K2 = std::integral_constant<int, 2>;
   const int nfull = L / KV_TILE;
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
   if (active) {
-    for (int it = 0; it < nfull; ++it) tile(it, K2{}, std::false_type{});
+    int it = 0;
+    for (; it + 2 <= nfull; it += 2) {
+      tile(it, K2{}, std::false_type{}, B0{});
+      tile(it + 1, K2{}, std::false_type{}, B1{});
+    }
+    if (it < nfull) tile(it, K2{}, std::false_type{}, B0{});
     if (nfull < nkv) {
-      if (L - nfull * KV_TILE <= 32) tile(nfull, K1{}, std::true_type{});
-      else tile(nfull, K2{}, std::true_type{});
+      const bool one = L - nfull * KV_TILE <= 32;
+      if (nfull & 1) {
+        if (one) tile(nfull, K1{}, std::true_type{}, B1{});
+        else tile(nfull, K2{}, std::true_type{}, B1{});
+      } else {
+        if (one) tile(nfull, K1{}, std::true_type{}, B0{});
+        else tile(nfull, K2{}, std::true_type{}, B0{});
+      }
     }
   } else {
     // a wave whose 32 queries all lie past the end only keeps up its share of the tile traffic
