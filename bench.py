@@ -243,9 +243,7 @@ def bench_workload(name, steps, warmup, args, want_flat, want_cpu):
         small_calls[cname] = dict(step=int(i), parents=parents, children=children, D=int(D), call_us=round(us, 2),
                                   kernel_us=round(kus, 2), algorithmic_bytes=int(nbytes),
                                   achieved_GBps=round(nbytes / kus / 1e3, 1),
-                                  frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4),
-                                  frac_of_hbm_peak_less_event_floor=round(
-                                      nbytes / max(kus - floor_us, 1e-3) / 1e3 / PEAK_HBM_GBS, 4))
+                                  frac_of_hbm_peak=round(nbytes / kus / 1e3 / PEAK_HBM_GBS, 4))
         del vpar
     us = timed_us(lambda: br.leaf_reward(tree, z, kind, w_rew, lam, latent, rew, rs))
     nbytes = 4.0 * D * n_leaves + 4.0 * D
@@ -354,6 +352,75 @@ def bench_workload(name, steps, warmup, args, want_flat, want_cpu):
     return out
 
 
+OPS = ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2", "attention", "ln_modulate", "sde_step")
+
+
+def run_op(args):
+    """One kernel of the network alone, at a workload's shape and a given batch: the target of
+    `rocprofv3 --pmc ... -- python3 bench.py --op NAME --workload W --op-batch B` (counter runs want few
+    dispatches).  Inputs are N(0, 1) activations and N(0, 0.02) weights."""
+    import torch
+    from paper_2509_06040_amd import binding as br
+    from paper_2509_06040_amd import synth
+    dev = "cuda"
+    wl = synth.WORKLOADS[args.workload]
+    cfg = wl["model"]
+    sz = synth.model_sizes(cfg)
+    L, H, NH, D = sz["L"], cfg["hidden"], cfg["n_heads"], sz["D"]
+    B = args.op_batch or wl["n_cond"] * 2 ** len(wl["splits"])
+    M = B * L
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    rnd = lambda *shape: torch.randn(shape, generator=g, device=dev)
+    bf = torch.bfloat16
+    name = args.op
+    if name.startswith("gemm_"):
+        N, K, mode = {"gemm_qkv": (3 * H, H, 0), "gemm_proj": (H, H, 2), "gemm_fc1": (4 * H, H, 1), "gemm_fc2": (H, 4 * H, 2)}[name]
+        A, W, bias = rnd(M, K).to(bf), (rnd(N, K) * 0.02).to(bf), rnd(N)
+        if mode == 2:
+            out, mods = rnd(M, N), rnd(wl["n_cond"], N)
+            cond = (torch.arange(B, device=dev) % wl["n_cond"]).to(torch.int32)
+            call = lambda: br.op_gemm(br.BF16, 2, A, W, bias, out, mods=mods, gate_off=0, cond=cond, L=L)
+        else:
+            out = torch.empty((M, N), dtype=bf, device=dev)
+            call = lambda: br.op_gemm(br.BF16, mode, A, W, bias, out)
+        work, unit = 2.0 * M * N * K, "TFLOP/s"
+    elif name == "attention":
+        qkv, out = rnd(B, L, 3 * H).to(bf), torch.empty((B, L, H), dtype=bf, device=dev)
+        call = lambda: br.op_attention(br.BF16, qkv, out, NH)
+        work, unit = 4.0 * B * L * L * H, "TFLOP/s"
+    elif name == "ln_modulate":
+        x, out, mods = rnd(M, H), torch.empty((M, H), dtype=bf, device=dev), rnd(wl["n_cond"], 2 * H)
+        cond = (torch.arange(B, device=dev) % wl["n_cond"]).to(torch.int32)
+        call = lambda: br.op_ln_modulate(br.BF16, x, out, L, L, mods, 0, H, cond)
+        work, unit = 6.0 * M * H, "GB/s"
+    else:  # the fused SDE step on the widest frontier
+        tree = br.Tree(wl["T"], wl["splits"], wl["K"], n_tree=wl["n_cond"])
+        i = wl["T"] - 1
+        P = wl["n_cond"] * int(tree.width[i])
+        z, lp, v = rnd(wl["n_cond"] * tree.n_nodes, D), torch.empty(wl["n_cond"] * tree.n_nodes, device=dev), rnd(P, D)
+        sched = synth.schedule(wl["T"], wl["kappa"])
+        scr = torch.empty(max(256, br.sde_scratch_bytes(tree, D)), dtype=torch.uint8, device=dev)
+        call = lambda: br.sde_step(tree, sched, 5, i, D, v, z, lp, scr)
+        work, unit, B = 12.0 * P * D, "GB/s", P
+    call()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(args.op_reps):
+        call()
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / args.op_reps
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+    print(json.dumps(dict(op=name, workload=args.workload, batch=B, rows=M, launches=args.op_reps + 1, avg_us=round(us, 2),
+                          achieved=round(work / us / (1e6 if unit == "TFLOP/s" else 1e3), 2), unit=unit)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -372,6 +439,10 @@ def main():
     ap.add_argument("--no-flat", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--op", default=None, choices=OPS, help="run one kernel alone at the shape of --workload (default "
+                    "image) and --op-batch samples instead of the benchmark; for counter collection")
+    ap.add_argument("--op-batch", type=int, default=0, help="samples in the batch of --op (default: the workload's widest frontier)")
+    ap.add_argument("--op-reps", type=int, default=3)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the measurement covers one GPU only (conditions are independent trees and would shard "
@@ -382,6 +453,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     br.load()
+    if args.op:
+        if args.workload == "all":
+            args.workload = "image"
+        return run_op(args)
 
     names = ORDER if args.workload == "all" else (args.workload,)
     head = HEADLINE if args.workload == "all" else args.workload

@@ -22,7 +22,11 @@ extern "C" {
  * BR_BF16 needs K % 64 == 0, lda % 8 == 0, ldw % 8 == 0; N % 4 == 0 always.
  * variant: bf16 kernel (-1 = automatic; 4 / 5 / 6 = 256x256 / 128x128 / 256x128 tile per workgroup,
  * 7 = persistent 256x256 streaming kernel, needs K % 128 == 0; bits 4..11 = column-group width of
- * the tile walk, 0 = the kernel's own choice). */
+ * the tile walk, 0 = the kernel's own choice; for the persistent kernel bits 12..19 / 20..23 = start
+ * delay step, in half microseconds, of workgroups that have / do not have a tile less than the longest
+ * tile list on their compute die: group g = (workgroup index on the die) / 4 % 8 starts g steps late;
+ * bits 20..23 hold the second of the two; bits 24..30 = rows of a row block of the tile walk in units
+ * of 8 tile rows, 0 = the kernel's own choice). */
 br_status br_op_gemm(int32_t dtype, int32_t epilogue, const void* A, int32_t lda, const void* W,
                      int32_t ldw, int32_t M, int32_t N, int32_t K, const float* bias, void* out,
                      int32_t ldo, const float* mods, int32_t mods_stride, int32_t gate_off,

@@ -80,7 +80,8 @@ br_status launch_gemm_bf16(int mode, const bf16* A, int lda, const bf16* W, int 
                            const EpiArgs& ea, int variant, hipStream_t st);
 bool gemm_stream_supported(int M, int N, int K, size_t bytes_a, size_t bytes_w);
 br_status launch_gemm_bf16_stream(int mode, const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K,
-                                  const EpiArgs& ea, int group_n, int stagger_slack, int stagger_crit, hipStream_t st);
+                                  const EpiArgs& ea, int group_n, int row_block, int stagger_slack, int stagger_crit,
+                                  hipStream_t st);
 br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st);
 br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, int rows_per_sample, int L_in, int H,
                              const float* mods, int A, int shift_off, int scale_off, const int* condmap,

@@ -222,7 +222,7 @@ static br_status gemm_dma_launch(const bf16* A, int lda, const bf16* W, int ldw,
 template <int MODE, typename TOUT>
 static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K, const EpiArgs& ea,
                               int variant, hipStream_t st) {
-  int tile, group_n = 0, stagger_slack = 0, stagger_crit = 0;
+  int tile, group_n = 0, row_block = 0, stagger_slack = 0, stagger_crit = 0;
   if (variant < 0) {
     // Measured on MI355X.  With r = (256x256 tiles) / (compute units):
     // up to half a round of tiles, 256x128 tiles put twice as many units to work; up to one
@@ -247,14 +247,15 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
     tile = variant & 15;
     group_n = (variant >> 4) & 255;
     stagger_slack = ((variant >> 12) & 255) * 50;  // half microseconds -> 10 ns ticks
-    stagger_crit = ((variant >> 20) & 255) * 50;
+    stagger_crit = ((variant >> 20) & 15) * 50;
+    row_block = ((variant >> 24) & 127) * 8;
   }
   ProfScope ps(st, PROF_GEMM + MODE * 8 + tile, 2.0 * M * N * K);
   switch (tile) {
     case 4: return gemm_dma_launch<256, 256, 2, 4, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 5: return gemm_dma_launch<128, 128, 2, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
     case 6: return gemm_dma_launch<256, 128, 4, 2, MODE, TOUT>(A, lda, W, ldw, M, N, K, ea, group_n, st);
-    case 7: return launch_gemm_bf16_stream(MODE, A, lda, W, ldw, M, N, K, ea, group_n, stagger_slack, stagger_crit, st);
+    case 7: return launch_gemm_bf16_stream(MODE, A, lda, W, ldw, M, N, K, ea, group_n, row_block, stagger_slack, stagger_crit, st);
   }
   return fail(BR_EINVAL, "gemm: unknown variant");
 }
