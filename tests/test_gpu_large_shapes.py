@@ -111,6 +111,107 @@ def test_video_shape_batch_of_eight_agrees_with_single_samples(video_case):
     assert len({r["v"][b].tobytes() for b in range(8)}) == 8
 
 
+def _tree_rollout(name, n_blocks, seed):
+    """The workload's own tree (all prompts, every frontier size) through br_rollout with a network
+    of n_blocks blocks; returns what the sampled-node checks below need."""
+    wl = synth.WORKLOADS[name]
+    cfg = _blocks(name, n_blocks)
+    D = synth.model_sizes(cfg)["D"]
+    C, T = wl["n_cond"], wl["T"]
+    W = synth.make_weights(cfg, seed, 0.02)
+    cond = synth.cond_tokens(cfg, C, seed + 1)
+    model = make_model(cfg, W)
+    t = br.Tree(T, wl["splits"], wl["K"], n_tree=C)
+    sched = synth.schedule(T, wl["kappa"], logp_mean=True)
+    n = C * t.n_nodes
+    z, v = torch.empty((n, D), device=DEV), torch.zeros((n, D), device=DEV)
+    logp = torch.empty(n, device=DEV)
+    ws = bytes_buffer(br.workspace_bytes(t, model, C * t.n_leaves))
+    br.rollout(t, model, sched, synth.SAMPLER_SEED, list(range(C)), cond_dev(cfg, cond), z, logp, v, ws)
+    torch.cuda.synchronize()
+    return dict(wl=wl, cfg=cfg, D=D, C=C, T=T, W=W, cond=cond, t=t, sched=sched, z=z, v=v, logp=logp,
+                o=tree.tree_build(T, wl["splits"], wl["K"]))
+
+
+def _check_transition(r, g):
+    """SDE step and log-prob of every child of global node g against the oracle, from the stored
+    latent and velocity of g (Eq. 2, App. B.1)."""
+    t, o, sched, D = r["t"], r["o"], r["sched"], r["D"]
+    seed = synth.SAMPLER_SEED
+    c, p = divmod(g, t.n_nodes)
+    i = int(t.depth[p])
+    zp, vp = host(r["z"][g]).astype(np.float64), host(r["v"][g]).astype(np.float64)
+    mu = sde.drift_mean(zp, vp, sched["t"][i], sched["t"][i + 1], sched["sigma"][i])
+    _, std = sde.step_coefficients(sched["t"][i], sched["t"][i + 1], sched["sigma"][i])
+    kids = tree.children(o, p)
+    xi0 = philox.normals(seed, g, i, philox.TAG_XI0, D) if len(kids) > 1 else None
+    for ch in kids:
+        gc = c * t.n_nodes + ch
+        eta = philox.normals(seed, gc, i, philox.TAG_ETA, D)
+        xi = sde.branch_noise(xi0, eta, sched["s"]) if xi0 is not None else eta
+        ref = mu + std * xi
+        assert np.abs(host(r["z"][gc]) - ref).max() < 2e-5
+        ref_lp = sde.transition_logp(ref, mu, std, True)
+        assert abs(float(host(r["logp"][gc])) - ref_lp) <= 1e-3 * abs(ref_lp)
+
+
+@pytest.fixture(scope="module")
+def large_tree(lib):
+    return _tree_rollout("image_large", 2, 21)
+
+
+# the large-image workload's tree (2 prompts, T = 16, splits {3,6,9,12}: frontiers of 2 to 32 samples) rolled
+# out by br_rollout with two blocks of its network; nodes of the smallest, a middle and the widest frontier,
+# one of them a split parent, against the oracle: velocity (teacher-forced on the stored latent) and the
+# transition to every child
+@pytest.mark.parametrize("depth,cond,j", [(1, 1, 0), (6, 0, 1), (14, 1, 13)])
+def test_large_image_tree_rollout_on_sampled_nodes(large_tree, depth, cond, j):
+    r = large_tree
+    t, cfg = r["t"], r["cfg"]
+    assert j < int(t.width[depth])
+    g = cond * t.n_nodes + int(t.off[depth]) + j
+    ref = dit.forward(cfg, r["W"], host(r["z"][g:g + 1]), float(r["sched"]["t"][depth]), r["cond"], [cond],
+                      act_round=dit.round_bf16)[0]
+    assert_velocity(cfg, host(r["v"][g]), ref, 2e-2, "large-image tree, depth %d (batch %d)" % (depth, 2 * int(t.width[depth])))
+    _check_transition(r, g)
+
+
+def test_large_image_tree_rollout_structure(large_tree):
+    r = large_tree
+    t, C = r["t"], r["C"]
+    lp = host(r["logp"]).reshape(C, -1)
+    assert np.all(lp[:, 0] == 0.0) and np.all(lp[:, 1:] != 0.0) and np.all(np.isfinite(lp))
+    z = r["z"].reshape(C, t.n_nodes, -1)
+    # siblings differ after a split, and differ from their parent; different prompts differ
+    for d in (4, 7, 10, 13):
+        a, b = int(t.off[d]), int(t.off[d]) + 1
+        assert int(t.parent[a]) == int(t.parent[b])
+        assert float((z[0, a] - z[0, b]).abs().max()) > 1e-3
+    assert float((z[0, 5] - z[1, 5]).abs().max()) > 1e-3
+
+
+@pytest.fixture(scope="module")
+def video_tree(lib):
+    return _tree_rollout("video", 1, 31)
+
+
+# the video workload's tree (1 prompt, T = 16, splits {4,8,12}: frontiers of 1 to 8 samples) with one block of
+# its network: sampled tokens of a node of the first and of the widest frontier, and their transitions
+@pytest.mark.parametrize("depth,j", [(2, 0), (13, 5)])
+def test_video_tree_rollout_on_sampled_nodes(video_tree, depth, j):
+    r = video_tree
+    t, cfg = r["t"], r["cfg"]
+    sz = synth.model_sizes(cfg)
+    g = int(t.off[depth]) + j
+    rows = np.sort(np.random.default_rng(depth).choice(sz["n_img"], 64, replace=False))
+    rows[0], rows[-1] = 0, sz["n_img"] - 1
+    ref = dit.forward_rows(cfg, r["W"], host(r["z"][g:g + 1]), float(r["sched"]["t"][depth]), r["cond"], [0], rows,
+                           act_round=dit.round_bf16)[0]
+    got = dit.patchify(cfg, host(r["v"][g:g + 1]).astype(np.float64))[0][rows]
+    assert_tokens(got, ref, 2e-2, "video tree, depth %d (batch %d)" % (depth, int(t.width[depth])))
+    _check_transition(r, g)
+
+
 def test_sde_step_and_video_reward_at_video_latent_size(lib):
     cfg = synth.WORKLOADS["video"]["model"]
     latent = (cfg["latent_c"], cfg["latent_t"], cfg["latent_h"], cfg["latent_w"])
