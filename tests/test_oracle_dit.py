@@ -100,6 +100,19 @@ def _torch_forward(cfg, W, z, t, cond, cond_index):
     return F.conv_transpose3d(o, eye, stride=(pt, ph, pw)).reshape(B, -1).numpy()
 
 
+def test_timestep_embedding_closed_form_values():
+    # sinusoid_256(1000 t) = [cos(1000 t f_k), sin(1000 t f_k)], f_k = 10000^(-k/128), k = 0..127
+    e0 = dit.timestep_embedding(0.0)
+    assert e0.shape == (256,) and np.array_equal(e0[:128], np.ones(128)) and np.array_equal(e0[128:], np.zeros(128))
+    e = dit.timestep_embedding(np.pi / 1000.0)                 # 1000 t = pi
+    assert abs(e[0] + 1.0) < 1e-12 and abs(e[128]) < 1e-12     # k = 0: f = 1 -> cos(pi), sin(pi)
+    assert abs(e[64] - np.cos(0.01 * np.pi)) < 1e-12           # k = 64: f = 10000^(-1/2) = 0.01
+    assert abs(e[128 + 64] - 0.031410759078128) < 1e-12        # sin(0.01 pi), written out
+    # the slowest frequency: f_127 = 10000^(-127/128); cos and sin are a unit vector per k
+    assert abs(e[127] - np.cos(np.pi * 10000.0 ** (-127.0 / 128.0))) < 1e-12
+    assert np.allclose(e[:128] ** 2 + e[128:] ** 2, 1.0, atol=1e-12)
+
+
 def test_forward_matches_independent_torch_composition():
     for cfg in (CFG, CFG_T):
         W = synth.make_weights(cfg, seed=3, std=0.2)        # large weights: every term matters
