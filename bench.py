@@ -47,7 +47,18 @@ ORDER = ("image", "video", "image_large")
 # then WRITE_SIZE, KiB per dispatch averaged over the launches of one step), each scaled by what the
 # same counter reads for a plain 1 GiB device copy; see profiles/hot_kernels_hbm_traffic.md.  Keyed
 # by (workload, kernel label); valid only for the kernel sources hashed beside the figures.
-TRAFFIC = {}
+TRAFFIC = {
+    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6623351654, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
+    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9199171277, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
+    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7171254784, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
+    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2158760090, sources=('attn_bf16.hip',), sha1='35b6d1e197b6bcbe4eb906a80c03f58b2f48f499'),
+    'image_large|ln_modulate': dict(bytes_per_launch=1213816259, sources=('dit_kernels.hip', 'common.h'), sha1='47fd7b9395ef1444ac93c6fd8f1cf48366314402'),
+    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=766276219, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
+    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=809864888, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
+    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=505419684, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
+    'image|attn_bf16[d64]': dict(bytes_per_launch=258854236, sources=('attn_bf16.hip',), sha1='35b6d1e197b6bcbe4eb906a80c03f58b2f48f499'),
+    'image|ln_modulate': dict(bytes_per_launch=193824707, sources=('dit_kernels.hip', 'common.h'), sha1='47fd7b9395ef1444ac93c6fd8f1cf48366314402'),
+}
 
 
 def measured_traffic(workload, label):
