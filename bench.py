@@ -52,12 +52,12 @@ TRAFFIC = {
     'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9199171277, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
     'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7171254784, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
     'image_large|attn_bf16[d128]': dict(bytes_per_launch=2158760090, sources=('attn_bf16.hip',), sha1='35b6d1e197b6bcbe4eb906a80c03f58b2f48f499'),
-    'image_large|ln_modulate': dict(bytes_per_launch=1213816259, sources=('dit_kernels.hip', 'common.h'), sha1='47fd7b9395ef1444ac93c6fd8f1cf48366314402'),
+    'image_large|ln_modulate': dict(bytes_per_launch=1213816259, sources=('dit_kernels.hip', 'common.h'), sha1='2d4467f4f19ce5252bf96c70383b154d1cb02902'),
     'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=766276219, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
     'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=809864888, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
     'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=505419684, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
     'image|attn_bf16[d64]': dict(bytes_per_launch=258854236, sources=('attn_bf16.hip',), sha1='35b6d1e197b6bcbe4eb906a80c03f58b2f48f499'),
-    'image|ln_modulate': dict(bytes_per_launch=193824707, sources=('dit_kernels.hip', 'common.h'), sha1='47fd7b9395ef1444ac93c6fd8f1cf48366314402'),
+    'image|ln_modulate': dict(bytes_per_launch=193824707, sources=('dit_kernels.hip', 'common.h'), sha1='2d4467f4f19ce5252bf96c70383b154d1cb02902'),
 }
 
 
@@ -74,7 +74,7 @@ def measured_traffic(workload, label):
     return round(t["bytes_per_launch"]) if h.hexdigest() == t["sha1"] else None
 
 
-HBM_KERNELS = {200: "sde_step", 201: "logp_eval", 300: "ln_modulate"}
+HBM_KERNELS = {200: "sde_step", 201: "logp_eval", 300: "ln_modulate", 301: "adaln_gemv"}
 
 
 def kernel_label(kid):
@@ -87,6 +87,19 @@ def kernel_label(kid):
 
 def progress(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+class Ticker:
+    """A progress line on stderr at most every `every` seconds (a long run must not fall silent)."""
+
+    def __init__(self, what, every=30.0):
+        self.what, self.every, self.last = what, every, time.perf_counter()
+
+    def tick(self, i, n):
+        now = time.perf_counter()
+        if now - self.last >= self.every:
+            self.last = now
+            progress("%s: %d of %d" % (self.what, i, n))
 
 
 def bench_workload(name, steps, warmup, args, want_flat, want_cpu):
@@ -166,14 +179,19 @@ def bench_workload(name, steps, warmup, args, want_flat, want_cpu):
             ev[3].record()
         return ev, nk
 
+    tick = Ticker("%s steps" % name)
     for i in range(warmup):
         step(synth.SAMPLER_SEED + i, False)
+        tick.tick(i + 1, warmup + steps)
     torch.cuda.synchronize()
     if not args.no_kernel_events:
         br.profile_enable(True)
         br.profile_read()
     t0 = time.perf_counter()
-    evs = [step(synth.SAMPLER_SEED + 100 + i, True) for i in range(steps)]
+    evs = []
+    for i in range(steps):
+        evs.append(step(synth.SAMPLER_SEED + 100 + i, True))
+        tick.tick(warmup + i + 1, warmup + steps)     # (the step has just waited for its kept-edge count: no extra stall)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = {}

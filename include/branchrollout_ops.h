@@ -52,7 +52,8 @@ br_status br_op_ln_modulate(int32_t dtype, const float* x, void* out, int32_t n_
  * recorded events, sums work (flops for GEMM and attention, bytes for the others)
  * and milliseconds per kernel id, clears the records and returns up to max_ids
  * entries.  Ids: GEMM = epilogue*8 + tile variant; attention = 100 + head dim;
- * 200 SDE step, 201 log-prob re-evaluation, 300 LayerNorm-modulate. */
+ * 200 SDE step, 201 log-prob re-evaluation, 300 LayerNorm-modulate, 301 adaLN modulation GEMV
+ * (bytes = the weights it streams). */
 br_status br_profile_enable(int32_t on);
 br_status br_profile_read(int32_t max_ids, int32_t* ids, double* work, double* ms,
                           int64_t* launches, int32_t* n_ids);

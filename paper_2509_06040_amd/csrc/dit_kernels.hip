@@ -203,6 +203,8 @@ static br_status conditioning_t(const br_model* m, const FwdBuffers& fb, const i
                      H, st)) != BR_OK) return s;
   hipLaunchKernelGGL(group_cvec_kernel, dim3(cdiv(H, 256), G), dim3(256), 0, st, fb.pool_lin, fb.ct, gcond, H, fb.cvec);
   BR_LAUNCH_CHECK();
+  // the modulation vectors of all blocks: a GEMV that streams the [A, H] weights once per 8 groups
+  ProfScope ps(st, PROF_ADALN, (double)cdiv(G, 8) * (double)m->A * H * sizeof(T));
   return skinny<T>(fb.cvec, H, G, (const T*)m->w[BR_W_ADA_W], H, m->A, (const float*)m->w[BR_W_ADA_B], nullptr, 0, 0,
                    fb.mods, m->A, st);
 }

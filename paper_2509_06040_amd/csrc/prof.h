@@ -9,6 +9,7 @@ enum ProfId {
   PROF_SDE_STEP = 200,
   PROF_LOGP_EVAL = 201,
   PROF_LN_MOD = 300,
+  PROF_ADALN = 301,     // the adaLN modulation GEMV (weight streaming)
 };
 bool prof_on();
 void prof_begin(hipStream_t st, int id, double work);  // work: flops or bytes of this launch
