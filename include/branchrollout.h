@@ -186,7 +186,9 @@ br_status br_rollout(const br_tree* tree, const br_model* model, const br_sched*
  * takes a time per sample group), so sparse kept-edge sets still fill the batch.
  *   edge_ids  host [n_edges], strictly ascending global child ids, none a root
  *   logp_out  dev out [n_edges]
- * Synchronises `stream` once while uploading its launch plan. */
+ * Asynchronous.  The launch plan built from edge_ids travels through a pinned staging buffer of the
+ * tree handle (allocated on first use); a second call on the same tree first waits, on the host, until
+ * the previous call's plan has left that buffer. */
 br_status br_logprob(const br_tree* tree, const br_model* model, const br_sched* sched,
                      const void* cond_tokens, const float* z_nodes, const int32_t* edge_ids,
                      int32_t n_edges, float* logp_out, void* workspace, size_t workspace_bytes,
@@ -261,7 +263,7 @@ br_status br_fusion_ess(const br_tree* tree, const float* logp_edges, float beta
 /* Velocity of a batch at one time (the network alone; used for teacher-forced
  * checks).  z dev [B, D] fp32; cond_index host [B] -> row of cond_tokens
  * (dev [n_cond, n_cond_tokens, cond_dim]); v_out dev [B, D] fp32.
- * Synchronises `stream` once while uploading cond_index. */
+ * Asynchronous (cond_index travels through a pinned staging buffer of the library, as in br_logprob). */
 br_status br_velocity(const br_model* model, const float* z, float t, const void* cond_tokens,
                       int32_t n_cond, const int32_t* cond_index, int32_t B, float* v_out,
                       void* workspace, size_t workspace_bytes, void* stream);

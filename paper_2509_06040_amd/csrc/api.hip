@@ -199,8 +199,7 @@ extern "C" br_status br_logprob(const br_tree* tree, const br_model* model, cons
     host[o_slot + e] = edges[e].slot;
   }
   BR_REQUIRE((long long)host.size() <= sz.plan_ints, BR_EWORKSPACE, "br_logprob: plan does not fit the workspace");
-  BR_HIP(hipMemcpyAsync(fb.plan, host.data(), host.size() * sizeof(int), hipMemcpyHostToDevice, st));
-  BR_HIP(hipStreamSynchronize(st));
+  if ((s = tree->plan_stage.upload(host.data(), host.size(), fb.plan, st)) != BR_OK) return s;
 
   if ((s = embed_cond(model, fb, cond_tokens, tree->n_tree, st)) != BR_OK) return s;
   const long long D = model->D;
@@ -261,9 +260,9 @@ extern "C" br_status br_velocity(const br_model* model, const float* z, float t,
   BR_REQUIRE(mb >= 1, BR_EWORKSPACE, "br_velocity: workspace too small");
   FwdBuffers fb;
   plan_workspace(model, n_cond, mb, 0, 0, B, &fb, workspace);
-  BR_HIP(hipMemcpyAsync(fb.plan, cond_index, (size_t)B * sizeof(int), hipMemcpyHostToDevice, st));
-  BR_HIP(hipStreamSynchronize(st));
+  static PinnedStage cond_stage;  // (shared by all callers of br_velocity; uploads are serialised)
   br_status s;
+  if ((s = cond_stage.upload(cond_index, (size_t)B, fb.plan, st)) != BR_OK) return s;
   if ((s = embed_cond(model, fb, cond_tokens, n_cond, st)) != BR_OK) return s;
   const SampleMap sm{nullptr, fb.plan, 0, 0, B};  // row = b
   for (int b0 = 0; b0 < B; b0 += mb) {

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_bf16.h>
 #include <stdint.h>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -58,6 +59,23 @@ __device__ inline void store4_stream(__bf16* p, float a, float b, float c, float
 
 }  // namespace br
 
+namespace br {
+// Pinned host staging for small host -> device uploads that must not make the caller wait: upload()
+// copies `n` ints into pinned memory owned by this object and enqueues the transfer on `st`.  Before
+// the pinned buffer is written again, the host waits for the previous transfer out of it (an event
+// recorded behind that transfer), which has long finished unless uploads follow each other
+// immediately.  The first use, and every growth, allocates (hipHostMalloc).  Serialised by a mutex.
+struct PinnedStage {
+  int* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool pending = false;
+  std::mutex mu;
+  br_status upload(const int* src, size_t n, int* dst_dev, hipStream_t st);
+  ~PinnedStage();
+};
+}  // namespace br
+
 struct br_tree {
   int T, K, n_tree, n_nodes, n_leaves;
   std::vector<int> splits;         // effective (empty when K == 1)
@@ -67,6 +85,7 @@ struct br_tree {
   // lazily created device mirror: off[T+2], parent, depth, leaf_lo, leaf_hi, first_child, n_child
   mutable int* d_mem = nullptr;
   mutable int d_device = -1;
+  mutable br::PinnedStage plan_stage;  // launch plans of br_logprob
   std::vector<int> first_child, n_child;
 };
 

@@ -35,6 +35,38 @@ int device_cu_count() {
   return cached[dev];
 }
 
+br_status PinnedStage::upload(const int* src, size_t n, int* dst_dev, hipStream_t st) {
+  if (n == 0) return BR_OK;
+  std::lock_guard<std::mutex> lock(mu);
+  if (pending) {  // the previous transfer reads the buffer: let it finish before overwriting
+    BR_HIP(hipEventSynchronize(ev));
+    pending = false;
+  }
+  if (n > cap) {
+    if (host) (void)hipHostFree(host);
+    host = nullptr;
+    cap = 0;
+    const size_t want = n + n / 2 + 256;
+    if (hipHostMalloc((void**)&host, want * sizeof(int), hipHostMallocDefault) != hipSuccess || !host) {
+      host = nullptr;
+      return fail(BR_ENOMEM, "pinned staging buffer: host allocation failed");
+    }
+    cap = want;
+  }
+  if (!ev) BR_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+  std::copy(src, src + n, host);
+  BR_HIP(hipMemcpyAsync(dst_dev, host, n * sizeof(int), hipMemcpyHostToDevice, st));
+  BR_HIP(hipEventRecord(ev, st));
+  pending = true;
+  return BR_OK;
+}
+
+PinnedStage::~PinnedStage() {
+  if (pending && ev) (void)hipEventSynchronize(ev);
+  if (host) (void)hipHostFree(host);
+  if (ev) (void)hipEventDestroy(ev);
+}
+
 br_status tree_device(const br_tree* t, TreeDev* out) {
   // one mirror per tree, created by br_tree_upload or by the first call that needs it; the
   // lock makes that first call safe when several threads share one tree
