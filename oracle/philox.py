@@ -8,12 +8,11 @@ by Salmon, Moraes, Dror and Shaw, "Parallel random numbers: as easy as 1, 2,
 3" (SC'11), keyed by the 64-bit seed, with the counter naming (element quad,
 node id, step, stream).
 
-Pins (tests/test_oracle_philox.py): the round function is a bijection with the
-inverse written from the definition; the normals pass moment, KS and
-independence checks; sibling covariance is 1/(1+s^2) (App. B.1).
-PARITY UNPINNED: the raw 32-bit words are not checked against the published
-known-answer vectors of that paper's software distribution (not available
-here); they are checked only by the GPU and CPU implementations agreeing.
+Pins (tests/test_oracle_philox.py): the raw words reproduce the generator's
+published known-answer vectors (all-zero, all-ones and pi-digit counter and
+key; tests/golden/philox4x32_10_known_answers.txt); the round function is a
+bijection with the inverse written from the definition; the normals pass
+moment, KS and independence checks; sibling covariance is 1/(1+s^2) (App. B.1).
 """
 import numpy as np
 

@@ -1,5 +1,7 @@
 """Pins for the oracle's noise generator (counter-based, Philox4x32-10 layout;
 requirement from Eq. 2 / App. B.1: xi_0, eta_b i.i.d. N(0, I), fresh per split)."""
+import os
+
 import numpy as np
 from scipy import stats
 
@@ -17,6 +19,18 @@ def _inverse_round(out, k0, k1):
     c0 = (o3 * inv0) & 0xFFFFFFFF
     hi1, hi0 = (M1 * c2) >> 32, (M0 * c0) >> 32
     return c0, o0 ^ hi1 ^ k0, c2, o2 ^ hi0 ^ k1
+
+
+def test_known_answer_vectors_of_the_published_generator():
+    """The raw words against the generator's published known answers (tests/golden/): fixes the
+    multipliers, the Weyl increments, the round count and the word order."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_known_answers.txt")
+    rows = [[int(w, 16) for w in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) == 3
+    for row in rows:
+        ctr, key, want = row[0:4], row[4:6], row[6:10]
+        got = philox.philox4x32_10(np.array([ctr], dtype=np.uint64), key[0] | (key[1] << 32))[0]
+        assert [int(x) for x in got] == want
 
 
 def test_round_is_a_bijection_with_the_defined_inverse():
