@@ -16,6 +16,7 @@
 // lane j receives element j of rows 0..3, so each lane ends up with four consecutive keys
 // of its own channel.
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 #include "dit.h"
@@ -30,6 +31,12 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define BR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(std::make_integer_sequence<int, N>{}, f); }
 
 constexpr int KV_TILE = 64;
 
@@ -67,6 +74,11 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
   constexpr int NPAR = RPI == 8 ? 2 : 4;    // distinct slot patterns among a wave's loads (the swizzle period is 16 rows)
   constexpr int ROW_B = CH * 16;            // bytes per row
   constexpr int TILE_B = KV_TILE * ROW_B;
+  // Operand fragments are read from LDS RA matrix instructions ahead of the one that consumes them
+  // (0: each read directly before its use, which is all that 128 registers leave room for).  With
+  // two waves a SIMD the LDS latency in front of every matrix instruction is otherwise exposed:
+  // 2-4 % of the launch at head dim 128; no gain was measured beyond two steps.
+  constexpr int RA = DH == 64 ? 0 : 2;
   __shared__ __attribute__((aligned(1024))) char sK[2][TILE_B];
   __shared__ __attribute__((aligned(1024))) char sV[2][TILE_B];
 
@@ -188,17 +200,39 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
 
     // S^T tile: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query l32
     f32x16 s[2];
+    if constexpr (RA == 0) {
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
+      for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      const int row = kb * 32 + l32;
+        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+        const int row = kb * 32 + l32;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int c = ks * 2 + lh;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) {
+          const int c = ks * 2 + lh;
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+        }
       }
+    } else {
+      constexpr int N = NKB * KS;
+      auto read_k = [&](int i) __attribute__((always_inline)) {
+        const int row = (i / KS) * 32 + l32, c = (i % KS) * 2 + lh;
+        return *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
+      };
+      bf16x8 kf[RA + 1];
+#pragma unroll
+      for (int i = 0; i < RA && i < N; ++i) kf[i] = read_k(i);
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      static_for<N>([&](auto Ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(Ic)::value;
+        if (i + RA < N) kf[(i + RA) % (RA + 1)] = read_k(i + RA);
+        __builtin_amdgcn_sched_barrier(0);
+        s[i / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (RA + 1)], qf[i % KS], s[i / KS], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      });
     }
     if (MASK) {  // keys past the end
 #pragma unroll
@@ -242,30 +276,63 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
 
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
     const char __attribute__((address_space(3)))* vt = (const char __attribute__((address_space(3)))*)BR_LPTR(sV[buf]);
+    if constexpr (RA == 0) {
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
+      for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        bf16x8 pf;
+        for (int j = 0; j < 2; ++j) {
+          bf16x8 pf;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[kb][8 * j + e];
-        // row sum of the rounded probabilities, two per instruction (what the product below sums)
+          for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[kb][8 * j + e];
+          // row sum of the rounded probabilities, two per instruction (what the product below sums)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const bf16x2 pr = {pf[e], pf[e + 1]};
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_run, false);
+          }
+#pragma unroll
+          for (int d = 0; d < DB; ++d) {
+            const auto* p0 = vt + vaddr[d] + (kb * 32 + j * 16) * ROW_B;
+            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+            const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * ROW_B));
+            union { s16x4 s[2]; bf16x8 v; } u;
+            u.s[0] = v0;
+            u.s[1] = v1;
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf, o[d], 0, 0, 0);
+          }
+        }
+    } else {
+      constexpr int N = 2 * NKB * DB;
+      auto read_v = [&](int i) __attribute__((always_inline)) {
+        const int st = i / DB, d = i % DB;  // step st = 2 kb + j covers keys 16 st .. 16 st + 15
+        const auto* p0 = vt + vaddr[d] + st * 16 * ROW_B;
+        union { s16x4 s[2]; bf16x8 v; } u;
+        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * ROW_B));
+        return u.v;
+      };
+      bf16x8 vf[RA + 1];
+#pragma unroll
+      for (int i = 0; i < RA && i < N; ++i) vf[i] = read_v(i);
+      bf16x8 pf[2 * NKB];
+#pragma unroll
+      for (int st = 0; st < 2 * NKB; ++st) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[st][e] = (bf16)s[st >> 1][8 * (st & 1) + e];
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-          const bf16x2 pr = {pf[e], pf[e + 1]};
+          const bf16x2 pr = {pf[st][e], pf[st][e + 1]};
           l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_run, false);
         }
-#pragma unroll
-        for (int d = 0; d < DB; ++d) {
-          const auto* p0 = vt + vaddr[d] + (kb * 32 + j * 16) * ROW_B;
-          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
-          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * ROW_B));
-          union { s16x4 s[2]; bf16x8 v; } u;
-          u.s[0] = v0;
-          u.s[1] = v1;
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf, o[d], 0, 0, 0);
-        }
       }
+      static_for<N>([&](auto Ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(Ic)::value;
+        if (i + RA < N) vf[(i + RA) % (RA + 1)] = read_v(i + RA);
+        __builtin_amdgcn_sched_barrier(0);
+        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % (RA + 1)], pf[i / DB], o[i % DB], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    }
     // the next tile has landed in this wave's share of the other buffer; after the barrier, in all of it
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
