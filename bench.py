@@ -25,6 +25,7 @@ for every workload that ran.
 import argparse
 import gc
 import json
+import math
 import os
 import sys
 import time
@@ -415,8 +416,12 @@ def run_op(args):
             call = lambda: br.op_gemm(br.BF16, mode, A, W, bias, out)
         work, unit = 2.0 * M * N * K, "TFLOP/s"
     elif name == "attention":
-        qkv, out = rnd(B, L, 3 * H).to(bf), torch.empty((B, L, H), dtype=bf, device=dev)
-        call = lambda: br.op_attention(br.BF16, qkv, out, NH)
+        # the layout the network's QKV projection writes: q carries log2(e) / sqrt(head dim)
+        x = rnd(B, L, 3 * H)
+        x[..., :H] *= math.log2(math.e) / math.sqrt(H // NH)
+        qkv, out = x.to(bf), torch.empty((B, L, H), dtype=bf, device=dev)
+        del x
+        call = lambda: br.op_attention(br.BF16, qkv, out, NH, q_prescaled=1)
         work, unit = 4.0 * B * L * L * H, "TFLOP/s"
     elif name == "ln_modulate":
         x, out, mods = rnd(M, H), torch.empty((M, H), dtype=bf, device=dev), rnd(wl["n_cond"], 2 * H)

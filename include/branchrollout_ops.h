@@ -34,9 +34,12 @@ br_status br_op_gemm(int32_t dtype, int32_t epilogue, const void* A, int32_t lda
 
 /* out[b, l, h*DH + d] = softmax_j(q_l . k_j / sqrt(DH)) v_j for every sample b and
  * head h; qkv dev [B, L, 3*NH*DH] (q | k | v), out dev [B, L, NH*DH], both `dtype`.
- * BR_BF16: DH 64 or 128, qkv 16-byte aligned, L*3*NH*DH*2 below 4 GiB (BR_ESHAPE otherwise). */
+ * BR_BF16: DH 64 or 128, qkv 16-byte aligned, L*3*NH*DH*2 below 4 GiB (BR_ESHAPE otherwise).
+ * q_prescaled = 1 (BR_BF16 only, BR_EINVAL otherwise): the q third holds q * log2(e) / sqrt(DH)
+ * instead of q -- the layout the network's QKV projection writes, which spares the kernel one
+ * multiplication per score; the result is the same function of the unscaled q. */
 br_status br_op_attention(int32_t dtype, const void* qkv, void* out, int32_t B, int32_t L,
-                          int32_t NH, int32_t DH, void* stream);
+                          int32_t NH, int32_t DH, int32_t q_prescaled, void* stream);
 
 /* out[r, :] = LayerNorm(x[src(r), :]) * (1 + scale) + shift, eps 1e-6, no affine;
  * r = b*rows_per_sample + tok, src(r) = b*L_in + tok; shift / scale are the rows

@@ -295,10 +295,10 @@ def op_gemm(dtype, epilogue, A, W, bias, out, mods=None, gate_off=0, cond=None, 
                              C.c_int32(gate_off), _p(cond), C.c_int32(L), C.c_int32(variant), _stream()))
 
 
-def op_attention(dtype, qkv, out, n_heads):
+def op_attention(dtype, qkv, out, n_heads, q_prescaled=0):
     B, L, H3 = qkv.shape
     _check(load().br_op_attention(C.c_int32(dtype), _p(qkv), _p(out), C.c_int32(B), C.c_int32(L), C.c_int32(n_heads),
-                                  C.c_int32(H3 // 3 // n_heads), _stream()))
+                                  C.c_int32(H3 // 3 // n_heads), C.c_int32(q_prescaled), _stream()))
 
 
 def op_ln_modulate(dtype, x, out, rows_per_sample, L_in, mods, shift_off, scale_off, cond):

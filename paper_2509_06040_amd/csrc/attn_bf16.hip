@@ -62,9 +62,12 @@ __device__ inline int v_swz(int r) { return DH == 128 ? ((r & 3) << 2) : (((r >>
 
 // With at most 256 registers a wave (two waves per SIMD) the compiler keeps the MFMA results in
 // ordinary vector registers, where the softmax works on them directly (accumulation registers
-// would cost a copy per element).  Head dim 64 fits in 128 registers: four waves per SIMD.
-template <int DH>
-__global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
+// would cost a copy per element).  Head dim 64 runs three waves per SIMD (168 registers: the
+// tile loop then spills nothing; a fourth wave bought no time).
+// PRE: the q third of the buffer already carries the factor log2(e) / sqrt(DH), as the network's
+// QKV projection writes it; otherwise the exponent is scaled here, one multiplication per score.
+template <int DH, bool PRE>
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out, int L,
                                                            int H, int NH, int n_pairs, int grouped, float scale_log2) {
   constexpr int CH = DH / 8;    // 16-byte chunks per K row
   constexpr int KS = DH / 16;   // MFMA k-steps of the score product
@@ -116,8 +119,15 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
   for (int d = 0; d < DB; ++d)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = 0.f, l_run = 0.f;  // reference (a bf16 value) and row sum of the probabilities taken against it
   const bf16x2 one2 = {(bf16)1.0f, (bf16)1.0f};
+  // the k-step that subtracts the reference: key side 1 in k-slot 0, query side -m_run there
+  bf16x8 onef, mf;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    onef[e] = (bf16)((e == 0 && lh == 0) ? 1.f : 0.f);
+    mf[e] = (bf16)0.f;
+  }
 
   // Key and value tiles go from global memory straight into LDS, 1 KB (RPI rows) per
   // instruction: lane i fills bytes 16 i .. 16 i + 15 of the instruction's span, so the chunk
@@ -198,81 +208,118 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
     // the other buffer was last read one tile ago, before the previous barrier
     issue(min(it + 1, nkv - 1) * KV_TILE, buf ^ 1);
 
-    // S^T tile: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query l32
+    // S^T tile minus the reference: s[kb][r] = score of key k0 + 32 kb + 8 (r/4) + 4 lh + r%4 for query
+    // l32, less m_run of that query.  The subtraction rides on the matrix pipe: one more k-step whose
+    // key side is the constant 1 and whose query side is -m_run (exact in bf16).
     f32x16 s[2];
-    if constexpr (RA == 0) {
+    auto scores = [&]() __attribute__((always_inline)) {
+      if constexpr (RA == 0) {
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb) {
+        for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-        const int row = kb * 32 + l32;
+          for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(onef, mf, s[kb], 0, 0, 0);
+          const int row = kb * 32 + l32;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const int c = ks * 2 + lh;
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+          for (int ks = 0; ks < KS; ++ks) {
+            const int c = ks * 2 + lh;
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+          }
+        }
+      } else {
+        constexpr int N = NKB * KS;
+        auto read_k = [&](int i) __attribute__((always_inline)) {
+          const int row = (i / KS) * 32 + l32, c = (i % KS) * 2 + lh;
+          return *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
+        };
+        bf16x8 kf[RA + 1];
+#pragma unroll
+        for (int i = 0; i < RA && i < N; ++i) kf[i] = read_k(i);
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(onef, mf, s[kb], 0, 0, 0);
+        }
+        static_for<N>([&](auto Ic) __attribute__((always_inline)) {
+          constexpr int i = decltype(Ic)::value;
+          if (i + RA < N) kf[(i + RA) % (RA + 1)] = read_k(i + RA);
+          __builtin_amdgcn_sched_barrier(0);
+          s[i / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (RA + 1)], qf[i % KS], s[i / KS], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      }
+      if (MASK) {  // keys past the end
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (key >= L) s[kb][r] = -INFINITY;
+          }
+      }
+    };
+    // p = 2^(s) (scores already in units of log2 e / sqrt(d)) or 2^(s scale): rounded to bf16 as the
+    // column operand of the second product, step 2 kb + j; l_tile = this lane's sum of the rounded
+    // values (what that product sums), two per instruction.
+    bf16x8 pf[2 * NKB];
+    float l_tile;
+    auto probabilities = [&]() __attribute__((always_inline)) {
+      l_tile = 0.f;
+#pragma unroll
+      for (int st = 0; st < 2 * NKB; ++st) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float x = s[st >> 1][8 * (st & 1) + e];
+          pf[st][e] = (bf16)__builtin_amdgcn_exp2f(PRE ? x : x * scale_log2);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const bf16x2 pr = {pf[st][e], pf[st][e + 1]};
+          l_tile = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_tile, false);
         }
       }
-    } else {
-      constexpr int N = NKB * KS;
-      auto read_k = [&](int i) __attribute__((always_inline)) {
-        const int row = (i / KS) * 32 + l32, c = (i % KS) * 2 + lh;
-        return *reinterpret_cast<const bf16x8*>(&sK[buf][(row * CH + (c ^ k_swz<DH>(row))) * 16]);
-      };
-      bf16x8 kf[RA + 1];
-#pragma unroll
-      for (int i = 0; i < RA && i < N; ++i) kf[i] = read_k(i);
-#pragma unroll
-      for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      static_for<N>([&](auto Ic) __attribute__((always_inline)) {
-        constexpr int i = decltype(Ic)::value;
-        if (i + RA < N) kf[(i + RA) % (RA + 1)] = read_k(i + RA);
-        __builtin_amdgcn_sched_barrier(0);
-        s[i / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (RA + 1)], qf[i % KS], s[i / KS], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      });
-    }
-    if (MASK) {  // keys past the end
+    };
+    // Softmax does not care which reference m is subtracted as long as numerator and denominator use
+    // the same one; here it is whatever the query's running maximum was when it last had to move.
+    // It has to move only when a probability would leave the comfortable range, and since
+    // probabilities are positive that shows in the row sum the kernel forms anyway: no maximum is
+    // taken on the way.  When some lane's sum of 32 probabilities passes 2^10 (or is not a number:
+    // overflow), and on a wave's first tile, the scores are formed once more, the reference follows
+    // the maximum (rounded to bf16; the accumulators are rescaled, 1 + DH/2 multiplications per lane)
+    // and the probabilities are taken again.  With an exact running maximum nearly every tile of a
+    // sequence rescales, and maximum, scale-and-subtract and rescale were half of the kernel's vector
+    // instructions -- which on this chip are not hidden behind the matrix instructions.
+    scores();
+    probabilities();
+    if (it == 0 || __builtin_amdgcn_ballot_w64(!(l_tile <= 1024.f)) != 0) {
+      scores();
+      float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          if (key >= L) s[kb][r] = -INFINITY;
-        }
-    }
-    // Reference maximum in the raw score domain (the scale is positive); the scale is folded into
-    // the exponent: p = exp2(s c - m c).  Softmax does not care which reference m is subtracted as
-    // long as numerator and denominator use the same one, so the reference follows the running
-    // maximum lazily: it moves (and the accumulators are rescaled, 1 + DH/2 multiplications per
-    // lane) only when some query of the wave has seen a score more than kSlack above it, i.e.
-    // when a probability would exceed 2^kSlack.  With an exact running maximum nearly every tile
-    // of a sequence rescales (one of 32 queries finds a new maximum), which was a third of the
-    // kernel's vector instructions -- and these are not hidden behind the matrix instructions.
-    constexpr float kSlack = 8.f;
-    float mx = -INFINITY;
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = (float)(bf16)(m_run + (it == 0 ? mx : fmaxf(mx, 0.f)));
+      const float delta = m_new - m_run;
+      if (it != 0) {
+        const float alpha = __builtin_amdgcn_exp2f(PRE ? -delta : -delta * scale_log2);
+        l_run *= alpha;
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
+        for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (__builtin_amdgcn_ballot_w64((mx - m_run) * scale_log2 > kSlack) != 0) {   // (-inf at the start: always)
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
-      l_run *= alpha;
+          for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      }
 #pragma unroll
-      for (int d = 0; d < DB; ++d)
+      for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+        for (int r = 0; r < 16; ++r) s[kb][r] -= delta;
       m_run = m_new;
+      mf[0] = lh == 0 ? (bf16)(-m_new) : (bf16)0.f;
+      probabilities();
     }
-    const float mc = m_run * scale_log2;
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -mc));
+    l_run += l_tile;
 
     // O^T += V^T P^T; k-slot (lh, e) of step (kb, j) is key 32 kb + 16 j + 8 (e/4) + 4 lh + e%4
     const char __attribute__((address_space(3)))* vt = (const char __attribute__((address_space(3)))*)BR_LPTR(sV[buf]);
@@ -281,15 +328,6 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
       for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          bf16x8 pf;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[kb][8 * j + e];
-          // row sum of the rounded probabilities, two per instruction (what the product below sums)
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            const bf16x2 pr = {pf[e], pf[e + 1]};
-            l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_run, false);
-          }
 #pragma unroll
           for (int d = 0; d < DB; ++d) {
             const auto* p0 = vt + vaddr[d] + (kb * 32 + j * 16) * ROW_B;
@@ -298,7 +336,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
             union { s16x4 s[2]; bf16x8 v; } u;
             u.s[0] = v0;
             u.s[1] = v1;
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf, o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[2 * kb + j], o[d], 0, 0, 0);
           }
         }
     } else {
@@ -314,17 +352,6 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
       bf16x8 vf[RA + 1];
 #pragma unroll
       for (int i = 0; i < RA && i < N; ++i) vf[i] = read_v(i);
-      bf16x8 pf[2 * NKB];
-#pragma unroll
-      for (int st = 0; st < 2 * NKB; ++st) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[st][e] = (bf16)s[st >> 1][8 * (st & 1) + e];
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          const bf16x2 pr = {pf[st][e], pf[st][e + 1]};
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, l_run, false);
-        }
-      }
       static_for<N>([&](auto Ic) __attribute__((always_inline)) {
         constexpr int i = decltype(Ic)::value;
         if (i + RA < N) vf[(i + RA) % (RA + 1)] = read_v(i + RA);
@@ -383,7 +410,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_bf16_kernel(const 
 }
 
 
-br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st) {
+br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, int q_prescaled, hipStream_t st) {
   BR_REQUIRE(L >= 1, BR_EINVAL, "attention: empty sequence");
   // the ragged last tile addresses its rows with 32-bit byte offsets from the sample's first row
   BR_REQUIRE((unsigned long long)L * 3ull * NH * DH * 2ull < (1ull << 32), BR_ESHAPE,
@@ -396,8 +423,13 @@ br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)DH));
   const int H = NH * DH;
   ProfScope ps(st, PROF_ATTN + DH, 4.0 * B * (double)L * L * H);
-  if (DH == 64) hipLaunchKernelGGL((attn_bf16_kernel<64>), g, blk, 0, st, qkv, out, L, H, NH, (int)n_pairs, grouped, scale_log2);
-  else if (DH == 128) hipLaunchKernelGGL((attn_bf16_kernel<128>), g, blk, 0, st, qkv, out, L, H, NH, (int)n_pairs, grouped, scale_log2);
+#define BR_ATTN_GO(DHc, PREc) \
+  hipLaunchKernelGGL((attn_bf16_kernel<DHc, PREc>), g, blk, 0, st, qkv, out, L, H, NH, (int)n_pairs, grouped, scale_log2)
+  if (DH == 64 && q_prescaled) BR_ATTN_GO(64, true);
+  else if (DH == 64) BR_ATTN_GO(64, false);
+  else if (DH == 128 && q_prescaled) BR_ATTN_GO(128, true);
+  else if (DH == 128) BR_ATTN_GO(128, false);
+#undef BR_ATTN_GO
   else return fail(BR_ESHAPE, "bf16 attention: head dim must be 64 or 128");
   BR_LAUNCH_CHECK();
   return BR_OK;

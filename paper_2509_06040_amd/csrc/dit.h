@@ -39,6 +39,10 @@ struct EpiArgs {
   const int* vrows;    // [B] destination row of each sample in v
   long long D;
   int lt, lh, lw, pt, ph, pw, gh, gw;
+  // EPI_BIAS: columns n < qcols (a multiple of 4) are multiplied by qscale after the bias.  The QKV
+  // projection of the bf16 network writes q * log2(e) / sqrt(head dim) this way, rounded to bf16 once.
+  int qcols;
+  float qscale;
 };
 
 struct FwdBuffers {  // carved from the workspace
@@ -75,14 +79,16 @@ br_status embed_cond(const br_model* m, const FwdBuffers& fb, const void* cond_t
 // ---- op launchers (dit_kernels.hip, gemm_bf16.hip, attn_bf16.hip)
 br_status launch_gemm(int dtype, int mode, const void* A, int lda, const void* W, int ldw, int M, int N, int K,
                       const EpiArgs& ea, hipStream_t st);
-br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, int NH, int DH, hipStream_t st);
+// q_prescaled: the q third already carries the factor log2(e) / sqrt(DH) (bf16 only)
+br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, int NH, int DH, int q_prescaled,
+                           hipStream_t st);
 br_status launch_gemm_bf16(int mode, const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K,
                            const EpiArgs& ea, int variant, hipStream_t st);
 bool gemm_stream_supported(int M, int N, int K, size_t bytes_a, size_t bytes_w);
 br_status launch_gemm_bf16_stream(int mode, const bf16* A, int lda, const bf16* W, int ldw, int M, int N, int K,
                                   const EpiArgs& ea, int group_n, int row_block, int stagger_slack, int stagger_crit,
                                   hipStream_t st);
-br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, hipStream_t st);
+br_status launch_attention_bf16(const bf16* qkv, bf16* out, int B, int L, int NH, int DH, int q_prescaled, hipStream_t st);
 br_status launch_ln_modulate(int dtype, const float* x, void* out, int n_rows, int rows_per_sample, int L_in, int H,
                              const float* mods, int A, int shift_off, int scale_off, const int* condmap,
                              hipStream_t st);
@@ -151,6 +157,8 @@ struct Epilogue {
   };
   static constexpr bool kHasAddend = MODE == EPI_BIAS_GATE_RES || MODE == EPI_PATCH_EMBED;
   __device__ inline float4 bias4(int n) const { return *reinterpret_cast<const float4*>(a.bias + n); }
+  // EPI_BIAS: factor of the four columns n..n+3 (n % 4 == 0)
+  __device__ inline float colscale(int n) const { return n < a.qcols ? a.qscale : 1.f; }
   __device__ inline SampleC sample_consts(int b, int n) const {
     SampleC s;
     s.gate = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -176,7 +184,8 @@ struct Epilogue {
                                 const SampleC& sc, const float4& add) const {
     v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
     if (MODE == EPI_BIAS) {
-      store4<T>(reinterpret_cast<T*>(a.out) + (long long)m * a.ldo + n, v0, v1, v2, v3);
+      const float cs = colscale(n);
+      store4<T>(reinterpret_cast<T*>(a.out) + (long long)m * a.ldo + n, v0 * cs, v1 * cs, v2 * cs, v3 * cs);
     } else if (MODE == EPI_BIAS_GELU) {
       store4<T>(reinterpret_cast<T*>(a.out) + (long long)m * a.ldo + n, gelu_tanh_f(v0), gelu_tanh_f(v1),
                 gelu_tanh_f(v2), gelu_tanh_f(v3));
@@ -216,7 +225,8 @@ struct Epilogue {
     const float4 bb = *reinterpret_cast<const float4*>(a.bias + n);
     v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
     if (MODE == EPI_BIAS) {
-      store4<T>(reinterpret_cast<T*>(a.out) + r.o + n, v0, v1, v2, v3);
+      const float cs = colscale(n);
+      store4<T>(reinterpret_cast<T*>(a.out) + r.o + n, v0 * cs, v1 * cs, v2 * cs, v3 * cs);
     } else if (MODE == EPI_BIAS_GELU) {
       store4<T>(reinterpret_cast<T*>(a.out) + r.o + n, gelu_tanh_f(v0), gelu_tanh_f(v1), gelu_tanh_f(v2),
                 gelu_tanh_f(v3));

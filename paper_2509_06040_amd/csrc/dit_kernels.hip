@@ -452,9 +452,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
   }
 }
 
-br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, int NH, int DH, hipStream_t st) {
+br_status launch_attention(int dtype, const void* qkv, void* out, int B, int L, int NH, int DH, int q_prescaled,
+                           hipStream_t st) {
   if (B == 0) return BR_OK;
-  if (dtype == BR_BF16) return launch_attention_bf16((const bf16*)qkv, (bf16*)out, B, L, NH, DH, st);
+  if (dtype == BR_BF16) return launch_attention_bf16((const bf16*)qkv, (bf16*)out, B, L, NH, DH, q_prescaled, st);
+  BR_REQUIRE(!q_prescaled, BR_EINVAL, "attention: prescaled queries are a bf16 layout");
   BR_REQUIRE(NH <= 65535 && B <= 65535, BR_ESHAPE, "attention: too many heads or samples for one launch");
   dim3 g(cdiv(L, 64), NH, B), blk(64);
   const float scale = 1.0f / sqrtf((float)DH);

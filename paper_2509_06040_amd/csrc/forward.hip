@@ -111,9 +111,13 @@ br_status forward(const br_model* m, const FwdBuffers& fb, const float* z_base, 
       ea.bias = (const float*)m->w[BR_W_QKV_B] + (size_t)k * 3 * H;
       ea.out = fb.qkv;
       ea.ldo = 3 * H;
+      if (dt == BR_BF16) {  // the attention kernel takes the scores in units of log2 e / sqrt(head dim)
+        ea.qcols = H;
+        ea.qscale = (float)(1.4426950408889634 / sqrt((double)m->DH));
+      }
       BR_TRY(launch_gemm(dt, EPI_BIAS, fb.xn, H, qkv_w, H, M, 3 * H, H, ea, st));
     }
-    BR_TRY(launch_attention(dt, fb.qkv, fb.xn, B, L, m->NH, m->DH, st));  // xn is free again: attention output
+    BR_TRY(launch_attention(dt, fb.qkv, fb.xn, B, L, m->NH, m->DH, dt == BR_BF16 ? 1 : 0, st));  // xn is free again: attention output
     {
       EpiArgs ea{};
       ea.bias = (const float*)m->w[BR_W_PROJ_B] + (size_t)k * H;

@@ -166,6 +166,12 @@ __device__ inline void wave_epilogue_bf16_full(const f32x16_e (&acc)[TN][TM], ch
           v1 = gelu_tanh_f(v1);
           v2 = gelu_tanh_f(v2);
           v3 = gelu_tanh_f(v3);
+        } else {
+          const float cs = epi.colscale(n_base + i * 32 + g * 8 + lh * 4);
+          v0 *= cs;
+          v1 *= cs;
+          v2 *= cs;
+          v3 *= cs;
         }
         const bf16x4_e pk = {(bf16)v0, (bf16)v1, (bf16)v2, (bf16)v3};
         *reinterpret_cast<bf16x4_e*>(wrow + (((i * 4 + g) ^ wswz) << 4)) = pk;

@@ -35,11 +35,13 @@ extern "C" br_status br_op_gemm(int32_t dtype, int32_t epilogue, const void* A, 
 }
 
 extern "C" br_status br_op_attention(int32_t dtype, const void* qkv, void* out, int32_t B, int32_t L, int32_t NH,
-                                     int32_t DH, void* stream) {
+                                     int32_t DH, int32_t q_prescaled, void* stream) {
   BR_REQUIRE(qkv && out, BR_EINVAL, "br_op_attention: NULL argument");
   BR_REQUIRE(dtype == BR_F32 || dtype == BR_BF16, BR_EINVAL, "br_op_attention: unknown dtype");
   BR_REQUIRE(B >= 1 && L >= 1 && NH >= 1, BR_EINVAL, "br_op_attention: bad sizes");
-  return launch_attention(dtype, qkv, out, B, L, NH, DH, (hipStream_t)stream);
+  BR_REQUIRE(q_prescaled == 0 || (q_prescaled == 1 && dtype == BR_BF16), BR_EINVAL,
+             "br_op_attention: q_prescaled is 0, or 1 with BR_BF16");
+  return launch_attention(dtype, qkv, out, B, L, NH, DH, q_prescaled, (hipStream_t)stream);
 }
 
 extern "C" br_status br_op_ln_modulate(int32_t dtype, const float* x, void* out, int32_t n_rows,

@@ -99,16 +99,64 @@ def test_attention_bf16(lib, dh, nh, L, B):
     assert err < 3e-3, err                       # bf16 probabilities and output rounding (measured 1.8e-3)
 
 
+@pytest.mark.parametrize("dh,nh,L,B", [(64, 2, 77, 2), (64, 4, 1101, 1), (128, 2, 130, 2), (128, 9, 257, 4), (64, 12, 63, 3)])
+def test_attention_bf16_prescaled_queries(lib, dh, nh, L, B):
+    """The layout the network's QKV projection writes: q * log2(e) / sqrt(dh) in the q third.  The
+    result is softmax attention of the q that these bf16 values stand for."""
+    rng = np.random.default_rng(dh + L)
+    H = nh * dh
+    c = np.log2(np.e) / np.sqrt(dh)
+    qkv = rng.standard_normal((B, L, 3 * H)).astype(np.float32) * 1.5
+    qkv[..., :H] *= c
+    qkv = _bf(qkv)
+    out = torch.full((B, L, H), 3.0, dtype=torch.bfloat16, device=DEV)
+    br.op_attention(br.BF16, dev(qkv, torch.bfloat16), out, nh, q_prescaled=1)
+    plain = qkv.astype(np.float64)
+    plain[..., :H] /= c
+    err = rel_l2(host(out), _attention_ref(plain, nh))
+    assert err < 3e-3, err
+    raw = br.load()
+    import ctypes as C
+    p = C.c_void_p(out.data_ptr())
+    assert raw.br_op_attention(br.F32, p, p, 1, 16, 2, 64, 1, None) == -1     # fp32 has no prescaled layout
+
+
+@pytest.mark.parametrize("jump", [40.0, -200.0])
+def test_attention_bf16_reference_follows_the_scores(lib, jump):
+    """jump > 0: keys 300.. score about `jump` (in powers of two) above everything before them, so
+    the kernel's softmax reference has to move mid-sequence.  jump < 0: every score sits that far
+    below zero, so the first tile must not start from a reference of zero."""
+    rng = np.random.default_rng(7)
+    dh, nh, L, B = 64, 2, 400, 1
+    H = nh * dh
+    qkv = rng.standard_normal((B, L, 3 * H)).astype(np.float32)
+    u = rng.standard_normal(dh).astype(np.float32)
+    u /= np.linalg.norm(u)
+    a = 4.0
+    b = jump * np.sqrt(dh) / np.log2(np.e) / a          # a b / sqrt(dh) * log2(e) = jump
+    for h in range(nh):
+        qkv[0, :, h * dh:(h + 1) * dh] += a * u
+        first = 300 if jump > 0 else 0
+        qkv[0, first:, H + h * dh:H + (h + 1) * dh] += b * u
+    qkv = _bf(qkv)
+    out = torch.full((B, L, H), 3.0, dtype=torch.bfloat16, device=DEV)
+    br.op_attention(br.BF16, dev(qkv, torch.bfloat16), out, nh)
+    got = host(out)
+    assert np.isfinite(got).all()
+    err = rel_l2(got, _attention_ref(qkv.astype(np.float64), nh))
+    assert err < 3e-3, err
+
+
 def test_attention_bf16_rejects_what_it_cannot_address(lib):
     import ctypes as C
     raw = br.load()
     buf = torch.zeros(64, dtype=torch.bfloat16, device=DEV)
     p = C.c_void_p(buf.data_ptr())
     # rows of one sample beyond 4 GiB (the check precedes any launch; the buffers are never touched)
-    assert raw.br_op_attention(br.BF16, p, p, 1, 400000, 16, 128, None) == -3
+    assert raw.br_op_attention(br.BF16, p, p, 1, 400000, 16, 128, 0, None) == -3
     assert b"4 GiB" in raw.br_last_error()
-    assert raw.br_op_attention(br.BF16, p, p, 1, 16, 2, 32, None) == -3          # head dim 32 in bf16
-    assert raw.br_op_attention(br.BF16, p, p, 1, 0, 2, 64, None) == -1
+    assert raw.br_op_attention(br.BF16, p, p, 1, 16, 2, 32, 0, None) == -3          # head dim 32 in bf16
+    assert raw.br_op_attention(br.BF16, p, p, 1, 0, 2, 64, 0, None) == -1
 
 
 @pytest.mark.parametrize("dt", [br.F32, br.BF16])
