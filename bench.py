@@ -49,16 +49,16 @@ ORDER = ("image", "video", "image_large")
 # same counter reads for a plain 1 GiB device copy; see profiles/hot_kernels_hbm_traffic.md.  Keyed
 # by (workload, kernel label); valid only for the kernel sources hashed beside the figures.
 TRAFFIC = {
-    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6623351654, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
-    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9199171277, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
-    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7171254784, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
-    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2158760090, sources=('attn_bf16.hip',), sha1='35b6d1e197b6bcbe4eb906a80c03f58b2f48f499'),
-    'image_large|ln_modulate': dict(bytes_per_launch=1213816259, sources=('dit_kernels.hip', 'common.h'), sha1='2d4467f4f19ce5252bf96c70383b154d1cb02902'),
-    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=766276219, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
-    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=809864888, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
-    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=505419684, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='4f6dd9645384e18bf6cef39a1810325ec60ccb06'),
-    'image|attn_bf16[d64]': dict(bytes_per_launch=258854236, sources=('attn_bf16.hip',), sha1='35b6d1e197b6bcbe4eb906a80c03f58b2f48f499'),
-    'image|ln_modulate': dict(bytes_per_launch=193824707, sources=('dit_kernels.hip', 'common.h'), sha1='2d4467f4f19ce5252bf96c70383b154d1cb02902'),
+    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6605218232, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
+    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9152061348, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
+    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7155499930, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
+    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2340403292, sources=('attn_bf16.hip',), sha1='f31cb7971e037cb6824cbd4abb1512d6a93454a6'),
+    'image_large|ln_modulate': dict(bytes_per_launch=1213816228, sources=('dit_kernels.hip', 'common.h'), sha1='b7256aef9d888386f0b9f9798816129e34b65ea7'),
+    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=765085379, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
+    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=806975560, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
+    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=499979745, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
+    'image|attn_bf16[d64]': dict(bytes_per_launch=258963251, sources=('attn_bf16.hip',), sha1='f31cb7971e037cb6824cbd4abb1512d6a93454a6'),
+    'image|ln_modulate': dict(bytes_per_launch=193824748, sources=('dit_kernels.hip', 'common.h'), sha1='b7256aef9d888386f0b9f9798816129e34b65ea7'),
 }
 
 
