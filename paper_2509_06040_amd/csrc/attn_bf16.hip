@@ -4,7 +4,7 @@
 //
 // Scores are computed transposed, S^T = K Q^T: in the 32x32 MFMA accumulator a
 // lane then holds 16 keys of ONE query (the other 16 sit in lane ^ 32), so the
-// running max / sum / rescale of the online softmax are per-lane scalars and the
+// reference / sum / rescale of the online softmax are per-lane scalars and the
 // exponentiated tile is already laid out as the column operand of O^T = V^T P^T.
 // The contraction order of that product is permuted to match the accumulator layout.
 //
@@ -78,9 +78,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bf16_kernel(const 
   constexpr int ROW_B = CH * 16;            // bytes per row
   constexpr int TILE_B = KV_TILE * ROW_B;
   // Operand fragments are read from LDS RA matrix instructions ahead of the one that consumes them
-  // (0: each read directly before its use, which is all that 128 registers leave room for).  With
-  // two waves a SIMD the LDS latency in front of every matrix instruction is otherwise exposed:
-  // 2-4 % of the launch at head dim 128; no gain was measured beyond two steps.
+  // (0: each read directly before its use, left to the compiler's scheduling).  With two waves a
+  // SIMD the LDS latency in front of every matrix instruction is otherwise exposed: 2-4 % of the
+  // launch at head dim 128, no more beyond two steps; nothing at head dim 64 with its three waves.
   constexpr int RA = DH == 64 ? 0 : 2;
   __shared__ __attribute__((aligned(1024))) char sK[2][TILE_B];
   __shared__ __attribute__((aligned(1024))) char sV[2][TILE_B];
