@@ -49,30 +49,39 @@ ORDER = ("image", "video", "image_large")
 # same counter reads for a plain 1 GiB device copy; see profiles/hot_kernels_hbm_traffic.md.  Keyed
 # by (workload, kernel label); valid only for the kernel sources hashed beside the figures.
 TRAFFIC = {
-    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6605218232, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
-    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9152061348, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
-    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7155499930, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
-    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2340403292, sources=('attn_bf16.hip',), sha1='f31cb7971e037cb6824cbd4abb1512d6a93454a6'),
-    'image_large|ln_modulate': dict(bytes_per_launch=1213816228, sources=('dit_kernels.hip', 'common.h'), sha1='b7256aef9d888386f0b9f9798816129e34b65ea7'),
-    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=765085379, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
-    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=806975560, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
-    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=499979745, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d39c7de33b388cecfbcb63a4f49a4e0134a5436e'),
-    'image|attn_bf16[d64]': dict(bytes_per_launch=258963251, sources=('attn_bf16.hip',), sha1='f31cb7971e037cb6824cbd4abb1512d6a93454a6'),
-    'image|ln_modulate': dict(bytes_per_launch=193824748, sources=('dit_kernels.hip', 'common.h'), sha1='b7256aef9d888386f0b9f9798816129e34b65ea7'),
+    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6605218232, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9152061348, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7155499930, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2340403292, sources=('attn_bf16.hip',), sha1='deb7cb68be1bb871d37e9d8f4121d812368a0ff2'),
+    'image_large|ln_modulate': dict(bytes_per_launch=1213816228, sources=('dit_kernels.hip', 'common.h'), sha1='123bdb315659e2bc89a1f7bd3071b9530aa623d9'),
+    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=765085379, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=806975560, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=499979745, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image|attn_bf16[d64]': dict(bytes_per_launch=258963251, sources=('attn_bf16.hip',), sha1='deb7cb68be1bb871d37e9d8f4121d812368a0ff2'),
+    'image|ln_modulate': dict(bytes_per_launch=193824748, sources=('dit_kernels.hip', 'common.h'), sha1='123bdb315659e2bc89a1f7bd3071b9530aa623d9'),
 }
 
 
 def measured_traffic(workload, label):
     """Counter-measured HBM bytes per launch, or None if there are none for this workload and kernel
     or the kernel sources changed since the counters were taken."""
-    import hashlib
     t = TRAFFIC.get("%s|%s" % (workload, label))
     if t is None:
         return None
+    return round(t["bytes_per_launch"]) if source_hash(t["sources"]) == t["sha1"] else None
+
+
+def source_hash(files):
+    """SHA-1 over the code of the given kernel sources: `//` comments and blank lines do not count."""
+    import hashlib
+    import re
     h = hashlib.sha1()
-    for f in t["sources"]:
-        h.update(open(os.path.join(ROOT, "paper_2509_06040_amd", "csrc", f), "rb").read())
-    return round(t["bytes_per_launch"]) if h.hexdigest() == t["sha1"] else None
+    for f in files:
+        for line in open(os.path.join(ROOT, "paper_2509_06040_amd", "csrc", f), encoding="utf-8"):
+            code = re.sub(r"//.*", "", line).rstrip()
+            if code:
+                h.update(code.encode() + b"\n")
+    return h.hexdigest()
 
 
 HBM_KERNELS = {200: "sde_step", 201: "logp_eval", 300: "ln_modulate", 301: "adaln_gemv"}
