@@ -228,9 +228,35 @@ static br_status gemm_variant(const bf16* A, int lda, const bf16* W, int ldw, in
     // up to half a round of tiles, 256x128 tiles put twice as many units to work; up to one
     // round the persistent 256x256 kernel is best; beyond that it stays best unless the last
     // round would be mostly empty (r = 1.08 costs two rounds), where 128x128 tiles win.
-    const long long t256 = (long long)cdiv(M, 256) * cdiv(N, 256);
-    const double r = (double)t256 / (double)device_cu_count();
+    const int cu = device_cu_count();
+    const long long tiles_m = cdiv(M, 256), tiles_n = cdiv(N, 256);
+    const long long t256 = tiles_m * tiles_n;
+    const double r = (double)t256 / (double)cu;
     const bool stream_ok = gemm_stream_supported(M, N, K, (size_t)M * lda * 2, (size_t)N * ldw * 2);
+    // One or two whole rounds and a last one that fills at most half the units: the rows are independent,
+    // so the matrix is cut in two launches, as many rows as make whole rounds for the persistent kernel and
+    // the rest -- at most half a round -- for the 256x128 tiles, which take half a tile time.  With
+    // per-sample epilogue operands the cut falls between two samples.  Measured on 1101-token samples:
+    // 3-16 % at 16 samples (1.1 to 4.3 rounds), 2-7 % at 24 and 32.  From three whole rounds on it does not
+    // pay: the few units of a sparse last round run faster than a full round's (64 samples, N = 1024,
+    // 4.3 rounds: 1-4 % slower when cut).
+    if (stream_ok && r > 1.0 && r < 3.0 && (MODE == EPI_BIAS || MODE == EPI_BIAS_GELU || MODE == EPI_BIAS_GATE_RES)) {
+      const long long whole = t256 / cu;
+      long long head_rows = (whole * cu / tiles_n) * 256;
+      const int rps = MODE == EPI_BIAS_GATE_RES ? ea.L : 256;
+      head_rows = head_rows / rps * rps;
+      const long long tail_rows = M - head_rows;
+      if (head_rows > 0 && tail_rows > 0 && cdiv(tail_rows, 256) * tiles_n * 2 <= cu &&
+          cdiv(head_rows, 256) * tiles_n <= whole * cu) {
+        EpiArgs tail = ea;
+        tail.out = (char*)ea.out + (size_t)head_rows * ea.ldo * sizeof(TOUT);
+        if (MODE == EPI_BIAS_GATE_RES) tail.condmap = ea.condmap + head_rows / rps;
+        const int head_variant = 7 | ((MODE == EPI_BIAS_GATE_RES && K <= 2048) ? (6 << 12) : 0);  // (the start stagger below)
+        const br_status head = gemm_variant<MODE, TOUT>(A, lda, W, ldw, (int)head_rows, N, K, ea, head_variant, st);
+        if (head != BR_OK) return head;
+        return gemm_variant<MODE, TOUT>(A + (size_t)head_rows * lda, lda, W, ldw, (int)tail_rows, N, K, tail, 6, st);
+      }
+    }
     if (r <= 0.5)
       tile = 6;
     else if (r > 1.0 && std::ceil(r) / r > 1.4)

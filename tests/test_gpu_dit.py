@@ -69,6 +69,43 @@ def test_gemm_gated_residual_epilogue(lib):
         assert rel_l2(host(x), ref) < tol
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_gemm_two_launch_cut_matches_one_launch_and_fp64(lib, mode):
+    """16 samples of 1101 tokens and 1024 output columns are 1.08 rounds of 256x256 tiles on 256
+    compute units: the library cuts the rows between two samples into a launch of the persistent
+    kernel and one of 256x128 tiles.  Same bits as the persistent kernel alone, and right against
+    fp64 on sampled rows on both sides of the cut (each sample with its own gate)."""
+    rng = np.random.default_rng(mode)
+    L, B, N, K, C = 1101, 16, 1024, 256, 5
+    M = L * B
+    A, W = _bf(rng.standard_normal((M, K)).astype(np.float32)), _bf(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
+    b = rng.standard_normal(N).astype(np.float32)
+    Ad, Wd, bd = dev(A, torch.bfloat16), dev(W, torch.bfloat16), dev(b)
+    rows = np.concatenate([np.arange(0, 3), np.arange(14 * L - 2, 14 * L + 3), np.arange(15 * L - 2, 15 * L + 2), np.arange(16382, 16387), np.arange(M - 3, M)])
+    lin = A[rows].astype(np.float64) @ W.astype(np.float64).T + b
+    if mode == 2:
+        x0 = rng.standard_normal((M, N)).astype(np.float32)
+        mods = rng.standard_normal((C, N)).astype(np.float32)
+        cond = (np.arange(B) * 3 % C).astype(np.int32)
+        outs = []
+        for variant in (-1, 7):
+            x = dev(x0.copy())
+            br.op_gemm(br.BF16, 2, Ad, Wd, bd, x, mods=dev(mods), gate_off=0, cond=dev(cond), L=L, variant=variant)
+            outs.append(x)
+        ref = x0[rows] + mods[cond[rows // L]] * lin
+        tol = 1e-5
+    else:
+        outs = []
+        for variant in (-1, 7):
+            out = torch.full((M, N), 3.0, dtype=torch.bfloat16, device=DEV)
+            br.op_gemm(br.BF16, mode, Ad, Wd, bd, out, variant=variant)
+            outs.append(out)
+        ref = dit.gelu_tanh(lin) if mode == 1 else lin
+        tol = 4e-3
+    assert torch.equal(outs[0], outs[1])
+    assert rel_l2(host(outs[0].float())[rows], ref) < tol
+
+
 def _attention_ref(qkv, nh):
     B, L, H3 = qkv.shape
     H = H3 // 3
