@@ -49,16 +49,16 @@ ORDER = ("image", "video", "image_large")
 # same counter reads for a plain 1 GiB device copy; see profiles/hot_kernels_hbm_traffic.md.  Keyed
 # by (workload, kernel label); valid only for the kernel sources hashed beside the figures.
 TRAFFIC = {
-    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6605218232, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
-    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9152061348, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
-    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7155499930, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
-    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2340403292, sources=('attn_bf16.hip',), sha1='deb7cb68be1bb871d37e9d8f4121d812368a0ff2'),
-    'image_large|ln_modulate': dict(bytes_per_launch=1213816228, sources=('dit_kernels.hip', 'common.h'), sha1='123bdb315659e2bc89a1f7bd3071b9530aa623d9'),
-    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=765085379, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
-    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=806975560, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
-    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=499979745, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
-    'image|attn_bf16[d64]': dict(bytes_per_launch=258963251, sources=('attn_bf16.hip',), sha1='deb7cb68be1bb871d37e9d8f4121d812368a0ff2'),
-    'image|ln_modulate': dict(bytes_per_launch=193824748, sources=('dit_kernels.hip', 'common.h'), sha1='123bdb315659e2bc89a1f7bd3071b9530aa623d9'),
+    'image_large|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=6612766740, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image_large|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=9183573064, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image_large|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=7166651914, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image_large|attn_bf16[d128]': dict(bytes_per_launch=2340423731, sources=('attn_bf16.hip',), sha1='deb7cb68be1bb871d37e9d8f4121d812368a0ff2'),
+    'image_large|ln_modulate': dict(bytes_per_launch=1213816248, sources=('dit_kernels.hip', 'common.h'), sha1='123bdb315659e2bc89a1f7bd3071b9530aa623d9'),
+    'image|gemm_bf16[bias_gate_residual,256x256 persistent stream]': dict(bytes_per_launch=636361196, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image|gemm_bf16[bias_gelu,256x256 persistent stream]': dict(bytes_per_launch=654394143, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image|gemm_bf16[bias,256x256 persistent stream]': dict(bytes_per_launch=502440038, sources=('gemm_bf16_stream.hip', 'gemm_epilogue.h', 'dit.h', 'common.h'), sha1='d08d8047b1b8c4977796a3d75174dee298cd7cee'),
+    'image|attn_bf16[d64]': dict(bytes_per_launch=258966323, sources=('attn_bf16.hip',), sha1='deb7cb68be1bb871d37e9d8f4121d812368a0ff2'),
+    'image|ln_modulate': dict(bytes_per_launch=193824737, sources=('dit_kernels.hip', 'common.h'), sha1='123bdb315659e2bc89a1f7bd3071b9530aa623d9'),
 }
 
 
