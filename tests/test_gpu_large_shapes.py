@@ -2,8 +2,9 @@
 4608 / 33272 tokens, 2M-element latents), at the batch sizes of the workloads' widest
 frontiers: batched networks of two blocks / one block teacher-forced against the oracle
 (bf16 tolerance 2e-2, per sample, per token and per element), the full frontier against the
-oracle-checked samples, the SDE step and the video reward at full latent size, and fusion,
-advantages and pruning on the two workloads' trees."""
+oracle-checked samples, the attention launch of each workload's shape on sampled queries, the SDE
+step and the video reward at full latent size, and fusion, advantages and pruning on the two
+workloads' trees."""
 import numpy as np
 import pytest
 import torch
@@ -210,6 +211,46 @@ def test_video_tree_rollout_on_sampled_nodes(video_tree, depth, j):
     got = dit.patchify(cfg, host(r["v"][g:g + 1]).astype(np.float64))[0][rows]
     assert_tokens(got, ref, 2e-2, "video tree, depth %d (batch %d)" % (depth, int(t.width[depth])))
     _check_transition(r, g)
+
+
+@pytest.mark.parametrize("name,B", [("video", 2), ("image_large", 3), ("image", 64)])
+def test_attention_at_full_size_on_sampled_queries(lib, name, B):
+    """The attention launch of the workload's shape (token count, heads, head dim; with 72 and
+    1024 (sample, head) pairs the order that keeps a pair on one XCD), queries in the layout the
+    QKV projection writes, against the oracle's attention on sampled query rows of the first and
+    the last sample: first and last rows, the rows around query- and key-tile boundaries, the
+    ragged tail."""
+    cfg = synth.WORKLOADS[name]["model"]
+    sz = synth.model_sizes(cfg)
+    L, H, nh = sz["n_img"], cfg["hidden"], cfg["n_heads"]
+    dh = H // nh
+    c = np.log2(np.e) / np.sqrt(dh)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(L + B)
+    x = torch.randn((B, L, 3 * H), device=DEV, generator=gen) * 1.5
+    x[..., :H] *= c
+    qkv = x.to(torch.bfloat16)
+    del x
+    out = torch.full((B, L, H), 3.0, dtype=torch.bfloat16, device=DEV)
+    br.op_attention(br.BF16, qkv, out, nh, q_prescaled=1)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, L // 2, L - 130, L - 129, L - 128,
+                                      L - (L % 64) - 1, L - (L % 64), L - 2, L - 1],
+                                     np.random.default_rng(L).choice(L, 24, replace=False)]) % L)
+    for b in (0, B - 1):
+        sample = qkv[b].float().cpu().numpy().astype(np.float64)
+        q = sample[rows, :H] / c
+        ref = dit.attention(q, sample[:, H:2 * H], sample[:, 2 * H:], nh)
+        got = out[b].float().cpu().numpy()[rows]
+        assert np.isfinite(got).all()
+        # all sampled rows together as in the small attention tests; every row; every element against its
+        # own size plus the rows' RMS (a head that looks at a dozen keys has elements ten times the RMS,
+        # and the output is rounded to bf16)
+        err = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        assert err < 3e-3, (name, b, err)
+        tok = np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)
+        assert tok.max() < 1e-2, (name, b, int(rows[tok.argmax()]), tok.max())
+        el = np.abs(got - ref) / (np.abs(ref) + np.sqrt((ref ** 2).mean()))
+        assert el.max() < 1e-2, (name, b, el.max())
 
 
 def test_sde_step_and_video_reward_at_video_latent_size(lib):
